@@ -1,0 +1,150 @@
+"""ctypes front end of the CPU oracle (oracle/intfa_oracle.c) -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this package.
+It imports nothing from the HIP package and shares no code with it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "intfa_oracle.c")
+_LIB = os.path.join(_HERE, "_intfa_oracle.so")
+
+# No fast-math, no contraction: every fp32 operation in the C file rounds once, as written.
+_CFLAGS = ["-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+           "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host gcc.  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *_CFLAGS, _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, i64, i32, f64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
+        lib.orc_num_threads.restype = ctypes.c_int
+        lib.orc_quantize_rows.argtypes = [vp, i64, i64, vp, vp]
+        lib.orc_qk_i32.argtypes = [vp, vp, i64, i32, vp]
+        lib.orc_pv_i32.argtypes = [vp, vp, i64, i32, vp]
+        lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
+                                               i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
+        lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
+        for f in (lib.orc_quantize_rows, lib.orc_qk_i32, lib.orc_pv_i32,
+                  lib.orc_int_flash_attn_fwd, lib.orc_attention_fp64):
+            f.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def num_threads() -> int:
+    return _load().orc_num_threads()
+
+
+def quantize_rows(X):
+    """X: real [rows, cols] (fp16/fp32, widened exactly to fp32).  -> (int8 [rows, cols], fp32 [rows])."""
+    X = _c(X, np.float32)
+    rows, cols = X.shape
+    q = np.empty((rows, cols), np.int8)
+    s = np.empty(rows, np.float32)
+    _load().orc_quantize_rows(_p(X), rows, cols, _p(q), _p(s))
+    return q, s
+
+
+def quantize_tokenwise(X):
+    """Token-level scheme of Q and K (Section 3.2): X [..., d] -> int8 same shape, scale [...]."""
+    X = np.asarray(X)
+    q, s = quantize_rows(X.reshape(-1, X.shape[-1]))
+    return q.reshape(X.shape), s.reshape(X.shape[:-1])
+
+
+def quantize_headwise(X, global_scale=False):
+    """Tensor-level scheme of V (Section 3.2): X [heads, N, d] -> int8 same shape, scale [heads].
+    global_scale=True uses one scale for the whole array, replicated to every head."""
+    X = np.asarray(X)
+    heads = X.shape[0]
+    if global_scale:
+        q, s = quantize_rows(X.reshape(1, -1))
+        return q.reshape(X.shape), np.full(heads, s[0], np.float32)
+    q, s = quantize_rows(X.reshape(heads, -1))
+    return q.reshape(X.shape), s
+
+
+def qk_i32(Q, K):
+    Q, K = _c(Q, np.int8), _c(K, np.int8)
+    N, d = Q.shape
+    S = np.empty((N, N), np.int32)
+    _load().orc_qk_i32(_p(Q), _p(K), N, d, _p(S))
+    return S
+
+
+def pv_i32(P, V):
+    P, V = _c(P, np.int8), _c(V, np.int8)
+    N, d = V.shape
+    out = np.empty((N, d), np.int32)
+    _load().orc_pv_i32(_p(P), _p(V), N, d, _p(out))
+    return out
+
+
+def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=None,
+                       tie_rel=0.0, tie_abs=0.0, want_P=False):
+    """Algorithm 1.  Q, K, V int8 [heads, N, d]; sQ, sK fp32 [heads, N]; sV fp32 [heads].
+    Returns a dict: O fp32 [rows, d], l, m fp32 [rows], n_tie int32 [rows], P int8 [rows, N] (if asked)."""
+    Q, K, V = _c(Q, np.int8), _c(K, np.int8), _c(V, np.int8)
+    heads, N, d = Q.shape
+    sQ, sK, sV = _c(sQ, np.float32), _c(sK, np.float32), _c(sV, np.float32)
+    assert K.shape == Q.shape and V.shape == Q.shape
+    assert sQ.shape == (heads, N) and sK.shape == (heads, N) and sV.shape == (heads,)
+    if row_idx is not None:
+        row_idx = _c(row_idx, np.int64)
+        n = row_idx.size
+        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * N)
+    else:
+        n = heads * N
+    O = np.empty((n, d), np.float32)
+    l = np.empty(n, np.float32)
+    m = np.empty(n, np.float32)
+    n_tie = np.zeros(n, np.int32)
+    P = np.empty((n, N), np.int8) if want_P else None
+    if n:
+        _load().orc_int_flash_attn_fwd(_p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), 1, heads, N, d,
+                                       int(bool(causal)), int(Bc), int(bool(p_quant)),
+                                       _p(row_idx), n, _p(O), _p(l), _p(m),
+                                       float(tie_rel), float(tie_abs), _p(n_tie), _p(P))
+    return {"O": O, "l": l, "m": m, "n_tie": n_tie, "P": P}
+
+
+def attention_fp64(Q, K, V, causal=False, scale=1.0, row_idx=None):
+    """Section 2.1 definition in fp64.  Q, K, V real [heads, N, d]."""
+    Q, K, V = _c(Q, np.float64), _c(K, np.float64), _c(V, np.float64)
+    heads, N, d = Q.shape
+    if row_idx is not None:
+        row_idx = _c(row_idx, np.int64)
+        n = row_idx.size
+    else:
+        n = heads * N
+    O = np.empty((n, d), np.float64)
+    if n:
+        _load().orc_attention_fp64(_p(Q), _p(K), _p(V), heads, N, d, int(bool(causal)), float(scale),
+                                   _p(row_idx), n, _p(O))
+    return O

@@ -1,0 +1,251 @@
+/*
+ * CPU oracle for the INT-FlashAttention forward pass -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, scalar restatement of what the method computes, written from the
+ * paper (arXiv 2409.16997) and sharing no code with the HIP path.  Only tests, the
+ * smoke check and the benchmark's cpu_baseline leg may call it; the product never does.
+ *
+ * Floating point follows the paper's statement that the scores S, the running max m,
+ * the running sum l and the on-chip output O are FP32 (Section 3.2, Figure 1 caption);
+ * integer products are exact int32.  Compile WITHOUT fast-math and with
+ * -ffp-contract=off so that every fp32 operation below rounds once, as written.
+ *
+ * Pins (tests/test_oracle_*.py): quantizer identity on the int8 grid, half-step error
+ * bound, sign symmetry; int32 GEMMs against int64 numpy; p_quant=0 against fp64
+ * brute-force attention; single-block closed form; uniform-score and one-hot closed
+ * forms; causal prefix properties; scale linearity; the P-rounding error bound.
+ * Unpinned: nothing in this file (the MRE magnitudes of Tables 1-2 are context only).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define R_INT8 127 /* Algorithm 1, Require: INT8 maximum R = 127 */
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Section 3.2 ("linear symmetric quantization", S = rowmax|X| / R).
+ * One scale per row of a [rows, cols] matrix: cols = d gives the token-level scheme of
+ * Q and K; rows = heads, cols = N*d gives the tensor-level scheme of V.
+ *   a = max|x|, s = a / 127, q = clamp(rint(x * (127 / a)), -127, 127); a == 0 -> s = 1, q = 0.
+ * All in fp32, round-half-to-even. */
+void orc_quantize_rows(const float *X, int64_t rows, int64_t cols, int8_t *q, float *s)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *x = X + r * cols;
+        int8_t *qr = q + r * cols;
+        float a = 0.0f;
+        for (int64_t k = 0; k < cols; ++k) {
+            float v = fabsf(x[k]);
+            if (v > a) a = v;
+        }
+        if (a == 0.0f) {
+            s[r] = 1.0f;
+            memset(qr, 0, (size_t)cols);
+            continue;
+        }
+        s[r] = a / 127.0f;
+        const float inv = 127.0f / a;
+        for (int64_t k = 0; k < cols; ++k) {
+            float t = rintf(x[k] * inv);
+            if (t > 127.0f) t = 127.0f;
+            if (t < -127.0f) t = -127.0f;
+            qr[k] = (int8_t)t;
+        }
+    }
+}
+
+/* Algorithm 1 line 9, integer part: S_int[i][j] = sum_k Q[i][k] * K[j][k], one head. */
+void orc_qk_i32(const int8_t *Q, const int8_t *K, int64_t N, int d, int32_t *S)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int32_t acc = 0;
+            for (int k = 0; k < d; ++k) acc += (int32_t)Q[i * d + k] * (int32_t)K[j * d + k];
+            S[i * N + j] = acc;
+        }
+}
+
+/* Algorithm 1 line 13, integer part: PV[i][c] = sum_j P[i][j] * V[j][c], one head. */
+void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i)
+        for (int c = 0; c < d; ++c) {
+            int32_t acc = 0;
+            for (int64_t j = 0; j < N; ++j) acc += (int32_t)P[i * N + j] * (int32_t)V[j * d + c];
+            PV[i * d + c] = acc;
+        }
+}
+
+/*
+ * Algorithm 1, one query row at a time (rows are independent, so B_r plays no role).
+ *
+ *   Q, K, V   int8 [B*H, N, d];  sQ, sK fp32 [B*H, N];  sV fp32 [B*H]
+ *   Bc        key-block size: the result depends on it, because block j is rounded on
+ *             the grid of the running max after block j, not of the final max.
+ *   causal    extension (not in the paper): key index > query index gets S = -inf, P = 0.
+ *   p_quant   1: Algorithm 1 (P rounded to int8, l sums the rounded P)
+ *             0: the FlashAttention-2 recurrence of Section 3.1 (P~ kept real), in fp64
+ *   row_idx   global row ids head*N + i to evaluate (NULL: all B*H*N rows in order)
+ *   O         fp32 [n_rows, d]
+ *   l_out, m_out   optional fp32 [n_rows]: final l and m
+ *   n_tie     optional int32 [n_rows]: number of P entries whose rounding would change if
+ *             the exponent argument moved by tie_rel * (|S| + |m|) + tie_abs; a different
+ *             fp32 evaluation order may legitimately round those the other way.
+ *   P_out     optional int8 [n_rows, N]: the rounded P of every key (p_quant = 1 only)
+ */
+void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
+                            const float *sQ, const float *sK, const float *sV,
+                            int B, int H, int64_t N, int d, int causal, int Bc, int p_quant,
+                            const int64_t *row_idx, int64_t n_rows,
+                            float *O, float *l_out, float *m_out,
+                            double tie_rel, double tie_abs, int32_t *n_tie, int8_t *P_out)
+{
+    const int64_t total = (int64_t)B * H * N;
+    if (row_idx == NULL) n_rows = total;
+
+#pragma omp parallel
+    {
+        float *S = (float *)malloc(sizeof(float) * (size_t)Bc);
+        int32_t *P = (int32_t *)malloc(sizeof(int32_t) * (size_t)Bc);
+        double *Pr = (double *)malloc(sizeof(double) * (size_t)Bc);
+        float *o = (float *)malloc(sizeof(float) * (size_t)d);
+        double *od = (double *)malloc(sizeof(double) * (size_t)d);
+
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const int64_t g = row_idx ? row_idx[r] : r;
+            const int64_t head = g / N, i = g % N;
+            const int8_t *q = Q + g * d;
+            const int8_t *Kh = K + head * N * d;
+            const int8_t *Vh = V + head * N * d;
+            const float sq = sQ[g];
+            const float *skh = sK + head * N;
+
+            float m = -INFINITY, l = 0.0f;   /* line 6 */
+            double ld = 0.0;
+            int32_t ties = 0;
+            for (int c = 0; c < d; ++c) { o[c] = 0.0f; od[c] = 0.0; }
+            if (P_out) memset(P_out + r * N, 0, (size_t)N);
+
+            for (int64_t j0 = 0; j0 < N; j0 += Bc) {              /* line 7 */
+                if (causal && j0 > i) break;
+                const int nb = (int)((N - j0 < Bc) ? (N - j0) : Bc);
+                float bmax = -INFINITY;
+                for (int jj = 0; jj < nb; ++jj) {                  /* line 9 */
+                    const int64_t j = j0 + jj;
+                    if (causal && j > i) { S[jj] = -INFINITY; continue; }
+                    const int8_t *k = Kh + j * d;
+                    int32_t acc = 0;
+                    for (int t = 0; t < d; ++t) acc += (int32_t)q[t] * (int32_t)k[t];
+                    S[jj] = ((float)acc * sq) * skh[j];
+                    if (S[jj] > bmax) bmax = S[jj];
+                }
+                const float m_new = (bmax > m) ? bmax : m;         /* line 10 */
+                const double alpha = (m == -INFINITY) ? 0.0 : exp((double)(m - m_new));
+
+                if (p_quant) {
+                    int32_t psum = 0;
+                    for (int jj = 0; jj < nb; ++jj) {              /* line 11 */
+                        if (S[jj] == -INFINITY) { P[jj] = 0; continue; }
+                        const float t = S[jj] - m_new;
+                        const double u = (double)R_INT8 * exp((double)t);
+                        P[jj] = (int32_t)nearbyint(u);
+                        psum += P[jj];
+                        if (n_tie) {
+                            const double half = floor(u) + 0.5;
+                            const double dt = tie_rel * (fabs((double)S[jj]) + fabs((double)m_new)) + tie_abs;
+                            if (fabs(u - half) <= u * dt) ++ties;
+                        }
+                        if (P_out) P_out[r * N + j0 + jj] = (int8_t)P[jj];
+                    }
+                    l = l * (float)alpha + (float)psum;            /* line 12 */
+                    for (int c = 0; c < d; ++c) {                  /* line 13 */
+                        int32_t pv = 0;
+                        for (int jj = 0; jj < nb; ++jj) pv += P[jj] * (int32_t)Vh[(j0 + jj) * d + c];
+                        o[c] = o[c] * (float)alpha + (float)pv;
+                    }
+                } else {
+                    double psum = 0.0;
+                    for (int jj = 0; jj < nb; ++jj) {
+                        Pr[jj] = (S[jj] == -INFINITY) ? 0.0 : exp((double)S[jj] - (double)m_new);
+                        psum += Pr[jj];
+                    }
+                    ld = ld * alpha + psum;
+                    for (int c = 0; c < d; ++c) {
+                        double pv = 0.0;
+                        for (int jj = 0; jj < nb; ++jj) pv += Pr[jj] * (double)Vh[(j0 + jj) * d + c];
+                        od[c] = od[c] * alpha + pv;
+                    }
+                }
+                m = m_new;
+            }
+
+            const float sv = sV[head];
+            if (p_quant) {
+                for (int c = 0; c < d; ++c) O[r * d + c] = (o[c] / l) * sv;   /* line 16 */
+                if (l_out) l_out[r] = l;
+            } else {
+                for (int c = 0; c < d; ++c) O[r * d + c] = (float)((od[c] / ld) * (double)sv);
+                if (l_out) l_out[r] = (float)ld;
+            }
+            if (m_out) m_out[r] = m;
+            if (n_tie) n_tie[r] = ties;
+        }
+        free(S); free(P); free(Pr); free(o); free(od);
+    }
+}
+
+/*
+ * Standard attention, Section 2.1: O = softmax(scale * Q K^T) V, row-wise softmax,
+ * fp64 throughout, written out as the definition (max, exponentials, sum, divide).
+ * Q, K, V are real [heads, N, d] in fp64.  `scale` is 1 for the paper's literal S = QK^T.
+ */
+void orc_attention_fp64(const double *Q, const double *K, const double *V,
+                        int64_t heads, int64_t N, int d, int causal, double scale,
+                        const int64_t *row_idx, int64_t n_rows, double *O)
+{
+    if (row_idx == NULL) n_rows = heads * N;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const int64_t g = row_idx ? row_idx[r] : r;
+            const int64_t head = g / N, i = g % N;
+            const double *q = Q + g * d;
+            const double *Kh = K + head * N * d;
+            const double *Vh = V + head * N * d;
+            const int64_t nk = causal ? i + 1 : N;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j < nk; ++j) {
+                double acc = 0.0;
+                for (int t = 0; t < d; ++t) acc += q[t] * Kh[j * d + t];
+                s[j] = acc * scale;
+                if (s[j] > mx) mx = s[j];
+            }
+            double sum = 0.0;
+            for (int64_t j = 0; j < nk; ++j) { s[j] = exp(s[j] - mx); sum += s[j]; }
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < nk; ++j) acc += s[j] * Vh[j * d + c];
+                O[r * d + c] = acc / sum;
+            }
+        }
+        free(s);
+    }
+}
