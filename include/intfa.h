@@ -1,0 +1,111 @@
+/*
+ * intfa -- INT-FlashAttention forward pass (arXiv 2409.16997) for AMD MI355X (gfx950).
+ *
+ * C ABI of libintfa.so.  Conventions shared by every entry point:
+ *   - Every pointer is a DEVICE pointer into memory the caller owns, valid until the work
+ *     enqueued by the call has finished, and 16-byte aligned.  The library keeps no pointer
+ *     after a call returns and allocates no memory.
+ *   - Tensors are contiguous and row-major: activations [B, H, N, d] with d fastest, per-token
+ *     scales [B, H, N], per-head scales [B, H].  The paper states everything for one head
+ *     [N, d]; batch and heads are independent copies of it.
+ *   - Calls enqueue kernels on a HIP stream and return without synchronising.  The stream is
+ *     the explicit argument where there is one, else the one given to ifa_set_stream()
+ *     (the null stream until then).
+ *   - Return value: IFA_OK (0) or a negative ifa_status.  On any error nothing is enqueued.
+ *     Arguments are validated on the host before a launch, so an unsupported shape is an
+ *     error code, never a device fault.
+ *   - R = 127 is the INT8 maximum of Algorithm 1 everywhere (quantizer grid and P grid).
+ */
+#ifndef INTFA_H
+#define INTFA_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { IFA_F32 = 0, IFA_F16 = 1, IFA_BF16 = 2 } ifa_dtype;
+
+typedef enum {
+    IFA_OK = 0,
+    IFA_ERR_NULL = -1,        /* a required pointer is null                                   */
+    IFA_ERR_SHAPE = -2,       /* a size is <= 0 or overflows the index range                  */
+    IFA_ERR_DTYPE = -3,       /* dtype enum out of range                                      */
+    IFA_ERR_UNSUPPORTED = -4, /* valid but not built: d, N granularity, misaligned pointer    */
+    IFA_ERR_HIP = -5          /* the HIP runtime refused the launch (hipGetLastError != 0)    */
+} ifa_status;
+
+/* Human-readable name of a status code (static storage, never null). */
+const char *ifa_status_str(int status);
+
+/* Sets the HIP stream (a hipStream_t passed as void*) used by the entry points that take no
+ * stream argument.  Process-wide; not thread-safe against concurrent calls.  Returns IFA_OK. */
+int ifa_set_stream(void *hip_stream);
+
+/*
+ * Token-level symmetric INT8 quantization of Q and K (Section 3.2: S_Q = rowmax|Q| / R,
+ * S_K = rowmax|K| / R, "linear symmetric quantization").
+ *   X       [rows, d] real activations of dtype x_dtype (ifa_dtype), rows = B*H*N
+ *   Xq      [rows, d] int8 out:  q = clamp(rint(x * (127 / a)), -127, 127), a = max_k |x[r,k]|
+ *   scale   [rows] fp32 out:     a / 127  (fp32 divide); an all-zero row gets scale 1, q = 0
+ * Arithmetic is fp32 with round-half-to-even and is bit-exact against that definition.
+ * d must be one of 32, 64, 128, 256, 512.  NaN/Inf inputs are outside the contract.
+ */
+int quantize_tokenwise(const void *X, int x_dtype, long rows, int d,
+                       signed char *Xq, float *scale);
+
+/*
+ * Tensor-level symmetric INT8 quantization of V (Section 3.2: S_V = max|V| / R, a single
+ * scalar for the head matrix V in R^{N x d}).
+ *   X       [heads, N, d] real activations, heads = B*H
+ *   Xq      [heads, N, d] int8 out, same rounding rule as quantize_tokenwise
+ *   scale   [heads] fp32 out.  global_scale = 0: one scalar per head (the paper's single-head
+ *           statement applied to each head).  global_scale = 1: one scalar for the whole
+ *           array, written to every slot.
+ * Uses `scale` itself as its only scratch (it holds the absmax between the two passes), so the
+ * array is read twice.  N*d must be a multiple of 8.
+ */
+int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d,
+                      signed char *Xq, float *scale, int global_scale);
+
+/*
+ * Algorithm 1 (INT-FlashAttention forward), lines 4-18, for every (b, h) head:
+ *   S = diag(s_Q) (Q K^T) diag(s_K)          int8 x int8 -> int32 on MFMA, then fp32 scales
+ *   m = max(m, rowmax S);  P = round(127 exp(S - m))  in [0, 127], int8
+ *   l = l e^{m_old - m} + rowsum(P);  O = e^{m_old - m} O + P V      int8 x int8 -> int32
+ *   O = diag(l)^-1 O s_V
+ * over key blocks of ifa_block_cols() keys, taken in ascending order (the result depends on
+ * that block size, because each block is rounded on the grid of the running max).
+ *   Q_i8, K_i8, V_i8   [B, H, N, d] int8
+ *   s_Q, s_K           [B, H, N] fp32, strictly positive;  s_V [B, H] fp32
+ *   causal             0: every key (the paper's setting); 1: key index <= query index only
+ *   O                  [B, H, N, d] out, fp16 for int_flash_attn_fwd, o_dtype for the _ex form
+ * There is no softmax scale: the paper's S has none.  A caller that wants 1/sqrt(d) multiplies
+ * s_Q by it (exact by the linearity remark of Section 3.2).
+ * Supported: d in {64, 128}; N a positive multiple of 128; B*H*N*d < 2^40.
+ */
+int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                       const float *s_Q, const float *s_K, const float *s_V,
+                       int B, int H, int N, int d, int causal, void *O);
+
+int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                          const float *s_Q, const float *s_K, const float *s_V,
+                          int B, int H, int N, int d, int causal, void *O, int o_dtype,
+                          void *hip_stream);
+
+/* B_c of Algorithm 1 as the kernel for (d, causal) uses it; 0 if that pair is unsupported. */
+int ifa_block_cols(int d, int causal);
+
+/*
+ * Test hooks: the exact int32 accumulators of the two GEMMs of Algorithm 1 (lines 9 and 13),
+ * produced by the same device tile code the fused kernel runs.  One head, N a multiple of 128.
+ *   ifa_debug_qk_i32:  S_i32 [N, N]  = Q_i8 [N, d] . K_i8 [N, d]^T
+ *   ifa_debug_pv_i32:  PV_i32 [N, d] = P_i8 [N, N] . V_i8 [N, d],  P in [0, 127]
+ * Both run on the ifa_set_stream() stream.
+ */
+int ifa_debug_qk_i32(const signed char *Q_i8, const signed char *K_i8, int N, int d, int *S_i32);
+int ifa_debug_pv_i32(const signed char *P_i8, const signed char *V_i8, int N, int d, int *PV_i32);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INTFA_H */

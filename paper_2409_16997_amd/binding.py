@@ -1,0 +1,145 @@
+"""ctypes binding of include/intfa.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libintfa.so")
+
+IFA_F32, IFA_F16, IFA_BF16 = 0, 1, 2
+
+# every symbol include/intfa.h declares, with its C signature
+_vp, _i, _l = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+SIGNATURES = {
+    "ifa_status_str": (ctypes.c_char_p, [_i]),
+    "ifa_set_stream": (_i, [_vp]),
+    "quantize_tokenwise": (_i, [_vp, _i, _l, _i, _vp, _vp]),
+    "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
+    "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
+    "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
+    "ifa_block_cols": (_i, [_i, _i]),
+    "ifa_debug_qk_i32": (_i, [_vp, _vp, _i, _i, _vp]),
+    "ifa_debug_pv_i32": (_i, [_vp, _vp, _i, _i, _vp]),
+}
+
+
+class IntfaError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C library.  Raises if it has not been built (no fallback of any kind)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise IntfaError(f"{_LIB_PATH} is missing: build it with `python -m paper_2409_16997_amd.build` "
+                             "or __graft_entry__.build(); there is no CPU fallback")
+        handle = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def status_str(code: int) -> str:
+    return lib().ifa_status_str(int(code)).decode()
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise IntfaError(f"{what}: {status_str(code)} ({code})")
+
+
+def _dtype_enum(t):
+    import torch
+    try:
+        return {torch.float32: IFA_F32, torch.float16: IFA_F16, torch.bfloat16: IFA_BF16}[t.dtype]
+    except KeyError:
+        raise IntfaError(f"unsupported dtype {t.dtype}") from None
+
+
+def _dev(t, dtype=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise IntfaError("expected a contiguous tensor in GPU memory")
+    if dtype is not None and t.dtype != dtype:
+        raise IntfaError(f"expected dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def quantize_tokenwise(X):
+    """X [..., d] fp32/fp16/bf16 on the GPU -> (int8 [..., d], fp32 scale [...])."""
+    import torch
+    d = X.shape[-1]
+    rows = X.numel() // d
+    Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
+    scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
+    L = lib()
+    L.ifa_set_stream(_stream())
+    _check(L.quantize_tokenwise(_dev(X), _dtype_enum(X), rows, d, _dev(Xq), _dev(scale)), "quantize_tokenwise")
+    return Xq, scale
+
+
+def quantize_headwise(X, global_scale=False):
+    """X [B, H, N, d] (or [heads, N, d]) -> (int8 same shape, fp32 scale [B, H] (or [heads]))."""
+    import torch
+    N, d = X.shape[-2], X.shape[-1]
+    heads = X.numel() // (N * d)
+    Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
+    scale = torch.empty(X.shape[:-2], dtype=torch.float32, device=X.device)
+    L = lib()
+    L.ifa_set_stream(_stream())
+    _check(L.quantize_headwise(_dev(X), _dtype_enum(X), heads, N, d, _dev(Xq), _dev(scale), int(bool(global_scale))),
+           "quantize_headwise")
+    return Xq, scale
+
+
+def int_flash_attn_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None):
+    """Algorithm 1 on [B, H, N, d] int8 tensors.  Returns O [B, H, N, d] (fp16 unless out_dtype/out says otherwise)."""
+    import torch
+    B, H, N, d = Q_i8.shape
+    if out is None:
+        out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
+    code = lib().int_flash_attn_fwd_ex(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
+                                       _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32),
+                                       B, H, N, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
+    _check(code, "int_flash_attn_fwd")
+    return out
+
+
+def block_cols(d: int, causal: bool) -> int:
+    return lib().ifa_block_cols(int(d), int(bool(causal)))
+
+
+def debug_qk_i32(Q_i8, K_i8):
+    import torch
+    N, d = Q_i8.shape
+    S = torch.empty((N, N), dtype=torch.int32, device=Q_i8.device)
+    L = lib()
+    L.ifa_set_stream(_stream())
+    _check(L.ifa_debug_qk_i32(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), N, d, _dev(S)), "ifa_debug_qk_i32")
+    return S
+
+
+def debug_pv_i32(P_i8, V_i8):
+    import torch
+    N, d = V_i8.shape
+    PV = torch.empty((N, d), dtype=torch.int32, device=V_i8.device)
+    L = lib()
+    L.ifa_set_stream(_stream())
+    _check(L.ifa_debug_pv_i32(_dev(P_i8, torch.int8), _dev(V_i8, torch.int8), N, d, _dev(PV)), "ifa_debug_pv_i32")
+    return PV

@@ -1,0 +1,222 @@
+// Symmetric INT8 quantizers of Section 3.2 (S = absmax / R, R = 127), gfx950.
+//
+// Both are HBM-streaming kernels: every element is read once (twice for V, whose scale needs
+// the whole head first) and written once as a byte.  A lane owns 8 consecutive elements, so
+// loads are 128-bit for fp16/bf16 and 2 x 128-bit for fp32, stores are 64-bit, and a row of
+// d elements is d/8 adjacent lanes whose absmax is combined with DPP lane shuffles.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+#include "intfa.h"
+#include "intfa_internal.h"
+
+namespace {
+
+// ---- 8 consecutive elements of any supported dtype, widened exactly to fp32 ------------------
+template <typename T> struct Load8;
+
+template <> struct Load8<float> {
+    static __device__ __forceinline__ void get(const void *p, long idx, float (&x)[8]) {
+        const float4 *q = reinterpret_cast<const float4 *>(static_cast<const float *>(p) + idx);
+        float4 a = q[0], b = q[1];
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+};
+template <> struct Load8<__half> {
+    static __device__ __forceinline__ void get(const void *p, long idx, float (&x)[8]) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const __half *>(p) + idx);
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { float2 f = __half22float2(h[i]); x[2 * i] = f.x; x[2 * i + 1] = f.y; }
+    }
+};
+template <> struct Load8<__hip_bfloat16> {
+    static __device__ __forceinline__ void get(const void *p, long idx, float (&x)[8]) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(static_cast<const __hip_bfloat16 *>(p) + idx);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                 // bf16 -> fp32 is a 16-bit shift
+            x[2 * i] = __uint_as_float(w[i] << 16);
+            x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+__device__ __forceinline__ float absmax8(const float (&x)[8]) {
+    float a = fmaxf(fabsf(x[0]), fabsf(x[1]));
+#pragma unroll
+    for (int i = 2; i < 8; ++i) a = fmaxf(a, fabsf(x[i]));
+    return a;
+}
+
+// q = clamp(rint(x * inv), -127, 127) for 8 values, packed little-endian into two dwords.
+__device__ __forceinline__ uint2 quant8(const float (&x)[8], float inv) {
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float t = rintf(x[i] * inv);
+        t = fminf(fmaxf(t, -127.0f), 127.0f);
+        w[i >> 2] |= (static_cast<uint32_t>(static_cast<int>(t)) & 0xffu) << (8 * (i & 3));
+    }
+    return make_uint2(w[0], w[1]);
+}
+
+// max over the aligned group of `LPR` adjacent lanes (LPR a power of two <= 64), result in all.
+template <int LPR>
+__device__ __forceinline__ float group_max(float a) {
+    // quad_perm [1,0,3,2] and [2,3,0,1], then mirrors inside 8 and 16 lanes: DPP, no LDS.
+    if (LPR >= 2) a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0xB1, 0xf, 0xf, true)));
+    if (LPR >= 4) a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x4E, 0xf, 0xf, true)));
+    if (LPR >= 8) a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x141, 0xf, 0xf, true)));  // row_half_mirror
+    if (LPR >= 16) a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x140, 0xf, 0xf, true))); // row_mirror
+    if (LPR >= 32) a = fmaxf(a, __shfl_xor(a, 16));
+    if (LPR >= 64) a = fmaxf(a, __shfl_xor(a, 32));
+    return a;
+}
+
+// ---- token-level: one row = LPR lanes ---------------------------------------------------------
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__restrict__ X, long rows,
+                                                                 int8_t *__restrict__ Xq,
+                                                                 float *__restrict__ scale) {
+    constexpr int D = LPR * 8;
+    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const long row_stride = static_cast<long>(gridDim.x) * ROWS_PER_BLOCK;
+    for (long row = static_cast<long>(blockIdx.x) * ROWS_PER_BLOCK + threadIdx.x / LPR; row < rows;
+         row += row_stride) {
+        float x[8];
+        const long idx = row * D + sub * 8;
+        Load8<T>::get(X, idx, x);
+        const float a = group_max<LPR>(absmax8(x));
+        const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
+        *reinterpret_cast<uint2 *>(Xq + idx) = quant8(x, inv);
+        if (sub == 0) scale[row] = (a == 0.0f) ? 1.0f : a / 127.0f;
+    }
+}
+
+// ---- tensor-level: absmax of a head, then quantize ---------------------------------------------
+// |x| >= 0, so the fp32 bit pattern orders like the value and an integer atomic max works.
+template <typename T>
+__global__ __launch_bounds__(256) void head_absmax_kernel(const void *__restrict__ X, long per_head,
+                                                          unsigned *__restrict__ amax_bits, int global_scale) {
+    const long head = blockIdx.y;
+    const long base = head * per_head;
+    float a = 0.0f;
+    for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < per_head;
+         i += static_cast<long>(gridDim.x) * 256 * 8) {
+        float x[8];
+        Load8<T>::get(X, base + i, x);
+        a = fmaxf(a, absmax8(x));
+    }
+    a = group_max<64>(a);
+    __shared__ float wmax[4];
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+        atomicMax(amax_bits + (global_scale ? 0 : head), __float_as_uint(a));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void head_quantize_kernel(const void *__restrict__ X, long per_head,
+                                                            const unsigned *__restrict__ amax_bits,
+                                                            int8_t *__restrict__ Xq, int global_scale) {
+    const long head = blockIdx.y;
+    const long base = head * per_head;
+    const float a = __uint_as_float(amax_bits[global_scale ? 0 : head]);
+    const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
+    for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < per_head;
+         i += static_cast<long>(gridDim.x) * 256 * 8) {
+        float x[8];
+        Load8<T>::get(X, base + i, x);
+        *reinterpret_cast<uint2 *>(Xq + base + i) = quant8(x, inv);
+    }
+}
+
+__global__ void zero_words_kernel(unsigned *p, long n) {
+    const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// absmax bits -> scale, in place.  One block; slot 0 is read by every thread before any write.
+__global__ void head_scale_finalize_kernel(float *scale, long heads, int global_scale) {
+    const float a0 = __uint_as_float(reinterpret_cast<const unsigned *>(scale)[0]);
+    __syncthreads();
+    for (long h = threadIdx.x; h < heads; h += blockDim.x) {
+        const float a = global_scale ? a0 : __uint_as_float(reinterpret_cast<const unsigned *>(scale)[h]);
+        scale[h] = (a == 0.0f) ? 1.0f : a / 127.0f;
+    }
+}
+
+template <typename T>
+int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, hipStream_t st) {
+    const int lpr = d / 8;
+    const long rows_per_block = 256 / lpr;
+    long blocks = (rows + rows_per_block - 1) / rows_per_block;
+    if (blocks > 256L * 64) blocks = 256L * 64;          // grid-stride beyond 64 blocks per CU
+    const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+    switch (lpr) {
+    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4>), grid, block, 0, st, X, rows, Xq, scale); break;
+    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8>), grid, block, 0, st, X, rows, Xq, scale); break;
+    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16>), grid, block, 0, st, X, rows, Xq, scale); break;
+    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32>), grid, block, 0, st, X, rows, Xq, scale); break;
+    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64>), grid, block, 0, st, X, rows, Xq, scale); break;
+    default: return IFA_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+}
+
+template <typename T>
+int launch_headwise(const void *X, long heads, long per_head, int8_t *Xq, float *scale, int global_scale,
+                    hipStream_t st) {
+    unsigned *bits = reinterpret_cast<unsigned *>(scale);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(static_cast<unsigned>((heads + 255) / 256)), dim3(256), 0, st, bits, heads);
+    long bx = (per_head / 8 + 255) / 256;
+    const long cap = (256L * 16 + heads - 1) / heads;   // about 16 blocks per CU in total
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(heads)), block(256);
+    hipLaunchKernelGGL((head_absmax_kernel<T>), grid, block, 0, st, X, per_head, bits, global_scale);
+    hipLaunchKernelGGL((head_quantize_kernel<T>), grid, block, 0, st, X, per_head, bits, Xq, global_scale);
+    hipLaunchKernelGGL(head_scale_finalize_kernel, dim3(1), dim3(256), 0, st, scale, heads, global_scale);
+    return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" int quantize_tokenwise(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale) {
+    if (!X || !Xq || !scale) return IFA_ERR_NULL;
+    if (rows <= 0 || d <= 0 || rows > (1L << 40) / d) return IFA_ERR_SHAPE;
+    if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
+    if (d != 32 && d != 64 && d != 128 && d != 256 && d != 512) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
+    hipStream_t st = ifa_current_stream();
+    int8_t *q = reinterpret_cast<int8_t *>(Xq);
+    switch (x_dtype) {
+    case IFA_F32: return launch_tokenwise<float>(X, rows, d, q, scale, st);
+    case IFA_F16: return launch_tokenwise<__half>(X, rows, d, q, scale, st);
+    default: return launch_tokenwise<__hip_bfloat16>(X, rows, d, q, scale, st);
+    }
+}
+
+extern "C" int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq,
+                                 float *scale, int global_scale) {
+    if (!X || !Xq || !scale) return IFA_ERR_NULL;
+    if (heads <= 0 || N <= 0 || d <= 0 || heads > 65535 || N > (1L << 40) / d / heads) return IFA_ERR_SHAPE;
+    if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
+    const long per_head = N * d;
+    if (per_head % 8 != 0) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
+    hipStream_t st = ifa_current_stream();
+    int8_t *q = reinterpret_cast<int8_t *>(Xq);
+    const int g = global_scale ? 1 : 0;
+    switch (x_dtype) {
+    case IFA_F32: return launch_headwise<float>(X, heads, per_head, q, scale, g, st);
+    case IFA_F16: return launch_headwise<__half>(X, heads, per_head, q, scale, g, st);
+    default: return launch_headwise<__hip_bfloat16>(X, heads, per_head, q, scale, g, st);
+    }
+}

@@ -1,0 +1,80 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol include/intfa.h declares,
+and rejects bad arguments on the host before any launch (no GPU needed: validation comes first)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2409_16997_amd as ifa
+    if not os.path.exists(ifa.lib_path()):
+        from paper_2409_16997_amd import build
+        build.build()
+    return ifa.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "intfa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|const char \*)\s*\*?\s*(\w+)\s*\(", text)))
+
+
+def test_header_declares_the_north_star_calls():
+    names = declared_symbols()
+    for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
+                 "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(L):
+    from paper_2409_16997_amd.binding import SIGNATURES
+    names = declared_symbols()
+    assert sorted(SIGNATURES) == names
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings(L):
+    assert L.ifa_status_str(0) == b"IFA_OK"
+    for c in (-1, -2, -3, -4, -5):
+        assert L.ifa_status_str(c).startswith(b"IFA_ERR_")
+    assert L.ifa_status_str(7) == b"unknown ifa_status"
+
+
+def test_block_cols(L):
+    assert L.ifa_block_cols(128, 1) == 128 and L.ifa_block_cols(64, 0) == 128
+    assert L.ifa_block_cols(96, 0) == 0
+
+
+def test_argument_validation_happens_on_the_host(L):
+    p = ctypes.c_void_p(0x1000)            # non-null, 16-byte aligned, never dereferenced by validation
+    null = ctypes.c_void_p(0)
+    odd = ctypes.c_void_p(0x1004)
+    f = L.int_flash_attn_fwd_ex
+    ok_tail = (p, 1, None)
+    assert f(null, p, p, p, p, p, 1, 1, 128, 128, 0, *ok_tail) == -1
+    assert f(p, p, p, p, p, p, 1, 1, 128, 128, 0, null, 1, None) == -1
+    assert f(p, p, p, p, p, p, 0, 1, 128, 128, 0, *ok_tail) == -2
+    assert f(p, p, p, p, p, p, 1, 1, -128, 128, 0, *ok_tail) == -2
+    assert f(p, p, p, p, p, p, 1, 1, 128, 128, 0, p, 9, None) == -3
+    assert f(p, p, p, p, p, p, 1, 1, 128, 96, 0, *ok_tail) == -4      # head dim not built
+    assert f(p, p, p, p, p, p, 1, 1, 100, 128, 0, *ok_tail) == -4     # ragged N not built
+    assert f(odd, p, p, p, p, p, 1, 1, 128, 128, 0, *ok_tail) == -4   # misaligned
+    assert L.int_flash_attn_fwd(null, p, p, p, p, p, 1, 1, 128, 128, 0, p) == -1
+    q = L.quantize_tokenwise
+    assert q(null, 1, 10, 128, p, p) == -1
+    assert q(p, 1, 0, 128, p, p) == -2
+    assert q(p, 5, 10, 128, p, p) == -3
+    assert q(p, 1, 10, 100, p, p) == -4
+    h = L.quantize_headwise
+    assert h(p, 1, 4, 128, 64, p, null, 0) == -1
+    assert h(p, 1, 0, 128, 64, p, p, 0) == -2
+    assert h(p, 3, 4, 128, 64, p, p, 0) == -3
+    assert h(p, 1, 4, 3, 3, p, p, 0) == -4
+    assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
+    assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1

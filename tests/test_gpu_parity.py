@@ -1,0 +1,284 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the same
+seeded inputs.  Bit-exact for the quantizers and the int32 GEMM accumulators; for O the bar is
+max|O_gpu - O_oracle| <= 1e-3 * max|O_oracle| (the benchmark spec's tolerance), plus, for the few rows where
+the oracle reports a P entry within fp32 evaluation noise of a rounding boundary, the exact effect one
+such entry rounding the other way can have on that row (either rounding is a valid Algorithm-1 result)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from helpers import quantized_inputs, random_int8_problem
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+# Window, in units of the exponent argument, inside which a different but equally valid fp32 evaluation
+# order (scales folded with log2 e, fused multiply-add, hardware exp2) may move 127*exp(S - m) across a
+# rounding boundary: a few roundings of relative size 2^-24 on |S| and |m|, plus the exp2 unit's error.
+TIE_REL = 8 * 2.0 ** -24
+TIE_ABS = 2e-6
+
+
+@pytest.fixture(scope="module")
+def ifa():
+    import paper_2409_16997_amd as m
+    m.lib()                      # raises if the HIP library is not built: there is no fallback
+    assert torch.cuda.is_available()
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bf16_round(x):               # fp32 -> bf16 (round half to even) -> fp32, on the host
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32)
+
+
+# ------------------------------------------------------------------ quantizers: bit-exact
+
+@pytest.mark.parametrize("dtype", ["float32", "float16", "bfloat16"])
+@pytest.mark.parametrize("rows,d", [(1, 64), (37, 128), (128, 64), (4099, 128), (1000, 32), (513, 256), (70, 512)])
+def test_quantize_tokenwise_bit_exact(ifa, dtype, rows, d):
+    rng = np.random.default_rng(rows * 1000 + d)
+    x = (rng.standard_t(3, (rows, d)) * rng.uniform(1e-3, 30, (rows, 1))).astype(np.float32)
+    x[rows // 2] = 0.0                                        # an all-zero token
+    if rows > 3:
+        x[1] = np.round(x[1])                                 # exact ties after scaling are likely here
+        x[2, :] = 0.0; x[2, 5] = -1.0                         # single non-zero
+    xt = torch.from_numpy(x).to(getattr(torch, dtype)).cuda()
+    xq, s = ifa.quantize_tokenwise(xt)
+    ref_q, ref_s = oracle.quantize_tokenwise(xt.float().cpu().numpy())    # widening is exact
+    assert np.array_equal(xq.cpu().numpy(), ref_q)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), ref_s.view(np.uint32))
+
+
+@pytest.mark.parametrize("dtype", ["float32", "float16"])
+@pytest.mark.parametrize("global_scale", [False, True])
+def test_quantize_headwise_bit_exact(ifa, dtype, global_scale):
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((2, 3, 384, 64)).astype(np.float32) * rng.uniform(0.1, 5, (2, 3, 1, 1)).astype(np.float32)
+    x[1, 1] = 0.0                                             # an all-zero head
+    xt = torch.from_numpy(x).to(getattr(torch, dtype)).cuda()
+    xq, s = ifa.quantize_headwise(xt, global_scale=global_scale)
+    ref_q, ref_s = oracle.quantize_headwise(xt.float().cpu().numpy().reshape(6, 384, 64), global_scale=global_scale)
+    assert np.array_equal(xq.cpu().numpy().reshape(6, 384, 64), ref_q)
+    assert np.array_equal(s.cpu().numpy().reshape(6).view(np.uint32), ref_s.view(np.uint32))
+
+
+def test_quantize_workload_heads_bit_exact(ifa):
+    for name in ("c1", "c2", "c4", "c5"):
+        w = workloads.WORKLOADS[name]
+        heads = [0, w.heads - 1] if w.heads > 1 else [0]
+        for t in ("Q", "V"):
+            x = workloads.tensor(w, t, heads)
+            xt = dev(x)
+            q, s = ifa.quantize_tokenwise(xt)
+            rq, rs = oracle.quantize_tokenwise(x)
+            assert np.array_equal(q.cpu().numpy(), rq) and np.array_equal(s.cpu().numpy(), rs)
+            q, s = ifa.quantize_headwise(xt)
+            rq, rs = oracle.quantize_headwise(x)
+            assert np.array_equal(q.cpu().numpy(), rq) and np.array_equal(s.cpu().numpy(), rs)
+
+
+# ------------------------------------------------------------------ int32 accumulators: bit-exact
+
+@pytest.mark.parametrize("N,d", [(128, 64), (128, 128), (384, 128), (256, 64)])
+def test_int32_gemm_accumulators_bit_exact(ifa, N, d):
+    rng = np.random.default_rng(N + d)
+    Q = rng.integers(-128, 128, (N, d), dtype=np.int8)
+    K = rng.integers(-128, 128, (N, d), dtype=np.int8)
+    V = rng.integers(-128, 128, (N, d), dtype=np.int8)
+    P = rng.integers(0, 128, (N, N), dtype=np.int8)
+    Q[0] = 127; K[1] = 127; K[2] = -128; Q[3] = -128          # extremes of the accumulator range
+    P[5] = 127; V[:, 7] = -128
+    S = ifa.debug_qk_i32(dev(Q), dev(K)).cpu().numpy()
+    assert np.array_equal(S, oracle.qk_i32(Q, K))
+    PV = ifa.debug_pv_i32(dev(P), dev(V)).cpu().numpy()
+    assert np.array_equal(PV, oracle.pv_i32(P, V))
+
+
+# ------------------------------------------------------------------ Algorithm 1 end to end
+
+def run_gpu(ifa, Qq, Kq, Vq, sQ, sK, sV, B, H, causal, out_dtype=None):
+    heads, N, d = Qq.shape
+    assert heads == B * H
+    sh = (B, H, N, d)
+    O = ifa.int_flash_attn_fwd(dev(Qq.reshape(sh)), dev(Kq.reshape(sh)), dev(Vq.reshape(sh)),
+                               dev(sQ.reshape(B, H, N)), dev(sK.reshape(B, H, N)), dev(sV.reshape(B, H)),
+                               causal=causal, out_dtype=out_dtype or torch.float32)
+    torch.cuda.synchronize()
+    return O
+
+
+def check_against_oracle(ifa, O_gpu_rows, Qq, Kq, Vq, sQ, sK, sV, causal, row_idx=None, label="", quiet=False):
+    d = Qq.shape[-1]
+    Bc = ifa.block_cols(d, causal)
+    ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc, row_idx=row_idx,
+                                    tie_rel=TIE_REL, tie_abs=TIE_ABS)
+    O_ref = ref["O"]
+    assert O_gpu_rows.shape == O_ref.shape
+    assert np.all(np.isfinite(O_gpu_rows))
+    scale = np.abs(O_ref).max()
+    err = np.abs(O_gpu_rows.astype(np.float64) - O_ref).max(axis=1)
+    heads_of_rows = (np.arange(O_ref.shape[0]) if row_idx is None else row_idx) // Qq.shape[1]
+    n_tie = ref["n_tie"].astype(np.float64)
+    # one P entry rounding the other way moves O[i, c] by |V_jc - O_ic| s_V / (l +- 1) <= 2*127*s_V / (l - n)
+    slack = n_tie * 2 * 127.0 * sV[heads_of_rows] / np.maximum(ref["l"] - n_tie, 1.0)
+    clean = n_tie == 0
+    worst_clean = (err[clean].max() / scale) if clean.any() else 0.0
+    if not quiet:
+        print(f"[parity {label}] rows={len(err)} max|dO|/max|O|={err.max() / scale:.3e} "
+              f"(rows without near-ties: {worst_clean:.3e}, rows with near-ties: {int((~clean).sum())})", flush=True)
+    assert np.all(err <= TOL * scale + slack), (err.max() / scale, int((err > TOL * scale + slack).sum()))
+    assert worst_clean <= TOL
+    return err.max() / scale, worst_clean, int((~clean).sum()), len(err)
+
+
+@pytest.mark.parametrize("scaled", [False, True])
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_small_workloads_every_element(ifa, name, scaled):
+    w = workloads.WORKLOADS[name]
+    x = quantized_inputs(w, scaled=scaled)
+    O = run_gpu(ifa, x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], w.B, w.H, w.causal).cpu().numpy()
+    check_against_oracle(ifa, O.reshape(-1, w.d), x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], w.causal,
+                         label=f"{name} scaled={scaled}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 128, 128), (1, 3, 256, 64), (2, 4, 384, 128), (1, 5, 640, 128), (1, 8, 512, 64)])
+@pytest.mark.parametrize("dist", ["normal", "uniform_outlier", "student_t3"])
+def test_shapes_masks_distributions(ifa, B, H, N, d, causal, dist):
+    # several key blocks, head counts that are and are not multiples of the XCD count, both head dims
+    w = workloads.custom("t", B, H, N, d, causal, dist=dist, seed=B * 1000 + N + d)
+    x = quantized_inputs(w, scaled=True)
+    O = run_gpu(ifa, x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], B, H, causal).cpu().numpy()
+    check_against_oracle(ifa, O.reshape(-1, d), x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], causal,
+                         label=f"{B}x{H}x{N}x{d} causal={causal} {dist}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_random_int8_grid_inputs_wide_scores(ifa, causal):
+    # int8 values over the whole range with score spreads from flat to nearly one-hot rows
+    rng = np.random.default_rng(5)
+    for sigma in (0.3, 2.0, 12.0):
+        Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 8, 256, 128, score_sigma=sigma)
+        O = run_gpu(ifa, Qq, Kq, Vq, sQ, sK, sV, 2, 4, causal).cpu().numpy()
+        check_against_oracle(ifa, O.reshape(-1, 128), Qq, Kq, Vq, sQ, sK, sV, causal, label=f"int8 sigma={sigma}")
+
+
+def test_degenerate_inputs(ifa):
+    rng = np.random.default_rng(6)
+    N, d = 256, 128
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 1, N, d)
+    # all-zero Q: every score is 0, every P is 127, O is the (prefix) mean of V
+    Z = np.zeros_like(Qq)
+    for causal in (False, True):
+        O = run_gpu(ifa, Z, Kq, Vq, sQ, sK, sV, 1, 1, causal).cpu().numpy().reshape(N, d)
+        Vh = Vq[0].astype(np.float64) * float(sV[0])
+        ref = np.cumsum(Vh, 0) / np.arange(1, N + 1)[:, None] if causal else np.broadcast_to(Vh.mean(0), (N, d))
+        assert np.allclose(O, ref, rtol=1e-5, atol=1e-7)
+    # all-zero V gives exactly zero
+    O = run_gpu(ifa, Qq, Kq, np.zeros_like(Vq), sQ, sK, sV, 1, 1, False).cpu().numpy()
+    assert not O.any()
+    # one dominant key (a one-hot softmax row): O is that value row exactly
+    Q1 = np.zeros_like(Qq); Q1[0, :, 0] = 100
+    K1 = np.zeros_like(Kq); K1[0, 3, 0] = 100
+    s = np.full((1, N), 0.03, np.float32)
+    O = run_gpu(ifa, Q1, K1, Vq, s, s, sV, 1, 1, False).cpu().numpy().reshape(N, d)
+    assert np.allclose(O, np.broadcast_to(Vq[0, 3].astype(np.float32) * sV[0], (N, d)), rtol=3e-7, atol=0)
+    # causal row 0 sees key 0 only
+    O = run_gpu(ifa, Qq, Kq, Vq, sQ, sK, sV, 1, 1, True).cpu().numpy().reshape(N, d)
+    assert np.allclose(O[0], Vq[0, 0].astype(np.float32) * sV[0], rtol=3e-7, atol=0)
+    # tiny and huge scales stay finite
+    O = run_gpu(ifa, Qq, Kq, Vq, sQ * np.float32(1e-6), sK, sV * np.float32(1e4), 1, 1, False).cpu().numpy()
+    assert np.all(np.isfinite(O))
+    check_against_oracle(ifa, run_gpu(ifa, Qq, Kq, Vq, sQ * 40, sK, sV, 1, 1, True).cpu().numpy().reshape(N, d),
+                         Qq, Kq, Vq, sQ * 40, sK, sV, True, label="sharp")
+
+
+def test_output_dtypes_and_determinism(ifa):
+    w = workloads.custom("t", 1, 8, 512, 128, True, seed=77)
+    x = quantized_inputs(w, scaled=True)
+    args = (x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], 1, 8, True)
+    O32 = run_gpu(ifa, *args, out_dtype=torch.float32).cpu().numpy()
+    O32b = run_gpu(ifa, *args, out_dtype=torch.float32).cpu().numpy()
+    assert np.array_equal(O32, O32b)                                      # same input twice: identical bits
+    O16 = run_gpu(ifa, *args, out_dtype=torch.float16).cpu().numpy()
+    assert np.array_equal(O16, O32.astype(np.float16))                    # epilogue = RNE cast of the fp32 result
+    Ob = run_gpu(ifa, *args, out_dtype=torch.bfloat16).float().cpu().numpy()
+    assert np.array_equal(Ob, bf16_round(O32))
+    # the 12-argument spec entry point writes fp16 on the stream given to ifa_set_stream
+    sh = (1, 8, 512, 128)
+    out = torch.empty(sh, dtype=torch.float16, device="cuda")
+    import ctypes
+    t = [dev(x["Qq"].reshape(sh)), dev(x["Kq"].reshape(sh)), dev(x["Vq"].reshape(sh)),
+         dev(x["sQ"].reshape(1, 8, 512)), dev(x["sK"].reshape(1, 8, 512)), dev(x["sV"].reshape(1, 8))]
+    L = ifa.lib()
+    L.ifa_set_stream(ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert L.int_flash_attn_fwd(*[ctypes.c_void_p(a.data_ptr()) for a in t], 1, 8, 512, 128, 1,
+                                ctypes.c_void_p(out.data_ptr())) == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), O16)
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled rows
+
+def _full_size(ifa, name, scaled, full_heads, rows_per_head):
+    w = workloads.WORKLOADS[name]
+    sh = (w.B, w.H, w.N, w.d)
+    Qd = torch.empty(sh, dtype=torch.int8, device="cuda")
+    Kd = torch.empty_like(Qd)
+    Vd = torch.empty_like(Qd)
+    sQd = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    sKd = torch.empty_like(sQd)
+    sVd = torch.empty((w.B, w.H), dtype=torch.float32, device="cuda")
+    sample = workloads.sample_rows(w, full_heads, rows_per_head)
+    kept = {}
+    fold = np.float32(1.0 / math.sqrt(w.d)) if scaled else np.float32(1.0)
+    for h in range(w.heads):                                   # oracle-quantized inputs, one head at a time
+        x = quantized_inputs(w, heads=[h])
+        sq = (x["sQ"] * fold).astype(np.float32)
+        b, hh = divmod(h, w.H)
+        Qd[b, hh].copy_(torch.from_numpy(x["Qq"][0])); Kd[b, hh].copy_(torch.from_numpy(x["Kq"][0]))
+        Vd[b, hh].copy_(torch.from_numpy(x["Vq"][0]))
+        sQd[b, hh].copy_(torch.from_numpy(sq[0])); sKd[b, hh].copy_(torch.from_numpy(x["sK"][0]))
+        sVd[b, hh] = float(x["sV"][0])
+        kept[h] = (x["Qq"][0], x["Kq"][0], x["Vq"][0], sq[0], x["sK"][0], x["sV"][0])
+    out_dtype = torch.float32                                  # parity on the fp32 result; casts are tested above
+    O = ifa.int_flash_attn_fwd(Qd, Kd, Vd, sQd, sKd, sVd, causal=w.causal, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all())
+    # oracle on the sampled rows, head by head (rows are independent)
+    worst, worst_clean, ties, n = 0.0, 0.0, 0, 0
+    for h, rows in sample:
+        Qq, Kq, Vq, sq, sk, sv = kept[h]
+        b, hh = divmod(h, w.H)
+        got = O[b, hh].cpu().numpy()[rows]
+        r = check_against_oracle(ifa, got, Qq[None], Kq[None], Vq[None], sq[None], sk[None],
+                                 np.array([sv], np.float32), w.causal, row_idx=rows, quiet=True)
+        worst, worst_clean, ties, n = max(worst, r[0]), max(worst_clean, r[1]), ties + r[2], n + r[3]
+    print(f"[parity {name} scaled={scaled}] sampled rows={n} max|dO|/max|O| per head={worst:.3e} "
+          f"(rows without near-ties: {worst_clean:.3e}, rows with near-ties: {ties})", flush=True)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("scaled", [True, False])
+def test_c3_full_size_sampled_rows(ifa, scaled):
+    _full_size(ifa, "c3", scaled, full_heads=1, rows_per_head=32)
+
+
+@pytest.mark.timeout(600)
+def test_c5_full_size_sampled_rows(ifa):
+    _full_size(ifa, "c5", True, full_heads=1, rows_per_head=64)
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size_sampled_rows(ifa):
+    _full_size(ifa, "c4", True, full_heads=1, rows_per_head=16)
