@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the INT-FlashAttention forward hot path on one MI355X.
+
+One "step" = the whole hot path over one batch of synthetic activations that are already resident in HBM:
+token-level INT8 quantization of Q and K, tensor-level quantization of V (Section 3.2) and the fused
+Algorithm-1 kernel.  The headline value is whole-step throughput in INT8 tera-operations per second
+(2 operations per multiply-accumulate of the two GEMMs, lower triangle only under the causal mask).
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the fused attention kernel), timed with HIP
+events on its own stream inside the timed region; `cpu_baseline` is the CPU oracle timed on the host cores
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5033.2      # MI355X dense INT8 MFMA: 256 CU x 4 SIMD x 1024 MAC/clk x 2 x 2.4 GHz
+
+
+def read_traffic(workload):
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"int_flash_attn_fwd_{workload}_pmc.txt")
+    try:
+        m = re.search(r"^HBM_BYTES_PER_LAUNCH\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", help="c1..c5 (default: the headline config, c3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
+    ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the method is a single-device operator; heads shard "
+                 "without communication). Run with --gpus 1.")
+
+    import torch
+    import workloads
+    import paper_2409_16997_amd as ifa
+
+    ifa.lib()                                   # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload]
+    sh = (w.B, w.H, w.N, w.d)
+    tdtype = {"float16": torch.float16, "float32": torch.float32}[w.in_dtype]
+    odtype = {"float16": torch.float16, "float32": torch.float32}[w.out_dtype]
+
+    # ---- synthetic activations, resident in HBM before anything is timed
+    Q = torch.empty(sh, dtype=tdtype, device=dev)
+    K = torch.empty_like(Q)
+    V = torch.empty_like(Q)
+    for h in range(w.heads):
+        b, hh = divmod(h, w.H)
+        Q[b, hh].copy_(torch.from_numpy(workloads.head_tensor(w, "Q", h)))
+        K[b, hh].copy_(torch.from_numpy(workloads.head_tensor(w, "K", h)))
+        V[b, hh].copy_(torch.from_numpy(workloads.head_tensor(w, "V", h)))
+    fold = 1.0 / math.sqrt(w.d)                 # softmax scale folded into s_Q (throughput does not depend on it)
+    O = torch.empty(sh, dtype=odtype, device=dev)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    state = {}
+
+    def step(i=None):
+        if not args.attn_only or "Qq" not in state:
+            Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
+            Kq, sK = ifa.quantize_tokenwise(K)
+            Vq, sV = ifa.quantize_headwise(V)
+            state.update(Qq=Qq, Kq=Kq, Vq=Vq, sQ=sQ, sK=sK, sV=sV)
+        s = state
+        if i is not None:
+            ev[i][0].record()
+        ifa.int_flash_attn_fwd(s["Qq"], s["Kq"], s["Vq"], s["sQ"], s["sK"], s["sV"], causal=w.causal, out=O)
+        if i is not None:
+            ev[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    attn_ms_min = float(np.min([a.elapsed_time(b) for a, b in ev]))
+    ops = w.ops
+    tops_step = ops / (ms_per_step * 1e-3) / 1e12
+    tops_attn = ops / (attn_ms * 1e-3) / 1e12
+    elems = w.heads * w.N * w.d
+    in_bytes = 2 if w.in_dtype == "float16" else 4
+    # algorithmic HBM bytes of the quantize passes: read once (V twice), write one byte, 4 bytes of scale per row
+    quant_bytes = elems * (3 * in_bytes + in_bytes + 3) + 4 * (2 * w.heads * w.N + w.heads)
+    quant_ms = max(ms_per_step - attn_ms, 1e-6)
+
+    result = {
+        "metric": "int8_attention_fwd_tops", "value": round(tops_step, 2), "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if w.causal else 'non-causal'} "
+                               f"{w.dist} {w.in_dtype} in, {w.out_dtype} out; step = quantize Q,K,V + fused attention",
+                   "block_cols": ifa.block_cols(w.d, w.causal), "softmax_scale": "1/sqrt(d) folded into s_Q",
+                   "ops_per_step": ops},
+        "pct_of_int8_mfma_peak": round(100 * tops_step / PEAK_INT8_TOPS, 2),
+        "roofline": {"bound": "mfma", "kernel": "int_flash_attn_fwd_kernel", "achieved": round(tops_attn, 2),
+                     "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": round(tops_attn / PEAK_INT8_TOPS, 4),
+                     "traffic": read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
+                     "min_launch_ms": round(attn_ms_min, 4),
+                     "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s"},
+        "quantize_pass": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
+                          "hbm_peak_GBps": 8000.0},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import baselines
+        # ---- oracle timed on the host cores on a bounded sample: whole heads of the same workload
+        n_heads = {"c1": 1, "c2": 64, "c3": 32, "c4": 2, "c5": 2}[w.name]
+        t_cpu = 0.0
+        worst = 0.0
+        for h in range(n_heads):
+            q, k, v = (workloads.head_tensor(w, t, h)[None] for t in "QKV")
+            t2 = time.perf_counter()
+            Qq, sQ = oracle.quantize_tokenwise(q)
+            Kq, sK = oracle.quantize_tokenwise(k)
+            Vq, sV = oracle.quantize_headwise(v)
+            sQ = (sQ * np.float32(fold)).astype(np.float32)
+            ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal))
+            t_cpu += time.perf_counter() - t2
+            if h < 2:                         # the timed oracle output doubles as a parity check of this run
+                b, hh = divmod(h, w.H)
+                got = O[b, hh].float().cpu().numpy()
+                worst = max(worst, float(np.abs(got - ref["O"]).max() / np.abs(ref["O"]).max()))
+        cpu_ops = ops * n_heads / w.heads
+        result["cpu_baseline"] = {"value": round(cpu_ops / t_cpu / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "seconds": round(t_cpu, 2),
+                                  "sample": f"{n_heads} of {w.heads} heads of {w.name} (all rows), quantize + Algorithm 1"}
+        result["parity_max_rel_err_vs_oracle"] = worst   # out-dtype rounding included (fp16 output: <= 2^-11 of |O|)
+
+        # ---- MRE against fp64 attention of the unquantized activations, beside fp16 and tensor-level FP8
+        h = 0
+        q, k, v = (workloads.head_tensor(w, t, h) for t in "QKV")
+        rows = np.arange(0, w.N, max(1, w.N // 256), dtype=np.int64)
+        ref64 = oracle.attention_fp64(q[None], k[None], v[None], causal=w.causal, scale=fold, row_idx=rows)
+        got = O[0, 0].float().cpu().numpy()[rows]
+        result["mre_vs_fp64"] = {
+            "rows": int(rows.size), "definition": "sum|dO|/sum|O| over sampled rows of head 0",
+            "int8_full (this kernel)": baselines.mre(got, ref64)["sum_ratio"],
+            "fp16": baselines.mre(baselines.attention_fp16(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
+            "fp8_e4m3_tensor_scale": baselines.mre(baselines.attention_fp8_tensor(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -53,6 +53,13 @@ int ifa_set_stream(void *hip_stream);
 int quantize_tokenwise(const void *X, int x_dtype, long rows, int d,
                        signed char *Xq, float *scale);
 
+/* Same, on an explicit stream, storing scale * scale_mul (one fp32 multiply after the divide) in
+ * place of the scale.  scale_mul = 1/sqrt(d) folds the usual softmax scale into s_Q, which by the
+ * linearity remark of Section 3.2 equals scaling S; Xq does not depend on it.  scale_mul must be a
+ * finite positive number (else IFA_ERR_SHAPE). */
+int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int d,
+                          signed char *Xq, float *scale, float scale_mul, void *hip_stream);
+
 /*
  * Tensor-level symmetric INT8 quantization of V (Section 3.2: S_V = max|V| / R, a single
  * scalar for the head matrix V in R^{N x d}).

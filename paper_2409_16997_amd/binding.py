@@ -15,6 +15,7 @@ SIGNATURES = {
     "ifa_status_str": (ctypes.c_char_p, [_i]),
     "ifa_set_stream": (_i, [_vp]),
     "quantize_tokenwise": (_i, [_vp, _i, _l, _i, _vp, _vp]),
+    "quantize_tokenwise_ex": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
@@ -81,16 +82,15 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def quantize_tokenwise(X):
-    """X [..., d] fp32/fp16/bf16 on the GPU -> (int8 [..., d], fp32 scale [...])."""
+def quantize_tokenwise(X, scale_mul=1.0):
+    """X [..., d] fp32/fp16/bf16 on the GPU -> (int8 [..., d], fp32 scale [...] times scale_mul)."""
     import torch
     d = X.shape[-1]
     rows = X.numel() // d
     Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
     scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
-    L = lib()
-    L.ifa_set_stream(_stream())
-    _check(L.quantize_tokenwise(_dev(X), _dtype_enum(X), rows, d, _dev(Xq), _dev(scale)), "quantize_tokenwise")
+    _check(lib().quantize_tokenwise_ex(_dev(X), _dtype_enum(X), rows, d, _dev(Xq), _dev(scale),
+                                       float(scale_mul), _stream()), "quantize_tokenwise")
     return Xq, scale
 
 

@@ -2,7 +2,9 @@
 //
 // Work split.  A workgroup of 4 wavefronts owns B_r = 128 query rows of one head, 32 per
 // wavefront, and walks the key blocks of B_c = 128 keys in ascending order (Algorithm 1 lines
-// 7-14).  K_j and V_j are staged once per workgroup in LDS; everything else lives in registers.
+// 7-14).  K_j, V_j and s_K,j are copied HBM -> LDS with direct-to-LDS 128-bit loads
+// (global_load_lds_dwordx4) into a double buffer, one block ahead of the arithmetic; everything
+// else lives in registers.
 //
 // Orientation.  Both GEMMs are computed transposed on v_mfma_i32_32x32x32_i8:
 //     S^T = K_j Q_i^T   (A = K_j rows from LDS, B = Q_i rows held in registers)
@@ -12,14 +14,17 @@
 // 32-key tile: row max and row sum are in-lane plus one exchange with lane ^ 32, and the 16 P
 // bytes a lane produces for a 32-key tile are exactly the 16 contraction bytes the B operand
 // of the second GEMM wants from that lane -- P never leaves registers.  The contraction index of
-// O^T = V^T P^T may be permuted freely as long as both operands agree, so V_j^T is written to LDS
-// with its keys in the order (tile, g, v) in which the accumulator layout delivers P.
+// O^T = V^T P^T may be permuted freely as long as both operands agree, so the V^T operand is
+// gathered with its keys in the order (tile, g, v) in which the accumulator layout delivers P.
 //
-// V_j is [keys, d] in HBM and the MFMA wants 16 consecutive KEYS per lane: the 4x4 byte transposes
-// happen once per workgroup on the way into LDS (v_perm_b32), not per wavefront.
+// V_j is [keys, d] in HBM and LDS, and the MFMA wants 16 KEYS of one d column per lane: that byte
+// transpose is done by the LDS itself with ds_read_b64_tr_b8 (per 16-lane group: lanes 0-7 receive
+// byte column i of the 8 rows addressed by the even lanes, lanes 8-15 of the rows addressed by the
+// odd lanes), two reads per MFMA operand, no VALU work.
 //
-// Softmax in base 2: s_K is pre-multiplied by log2(e) when it is staged, the running max m2 is kept
-// in log2 units and P = rint(exp2(a * s_Q - (m2 - log2 127))) with one v_exp_f32 per score.
+// Softmax in base 2: log2(e) is folded into s_Q once per lane, the running max m2 is kept in log2
+// units and P = rint(exp2(acc * s_K * s_Q' - (m2 - log2 127))) with one v_exp_f32 per score and
+// v_cvt_pk_u8_f32 (round-half-even, measured) packing four P bytes per dword.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
@@ -30,102 +35,112 @@
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+#define LDS_AS __attribute__((address_space(3)))
+#define GLOBAL_AS __attribute__((address_space(1)))
+typedef LDS_AS int8_t *lds_ptr;
 
 constexpr int BR = 128;       // query rows per workgroup
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
 constexpr int THREADS = 256;  // 4 wavefronts x 32 query rows
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
-constexpr float RNE_MAGIC = 12582912.0f;            // 1.5 * 2^23: x + MAGIC rounds x to an integer (ties to even)
 
 template <int D> struct Smem {
-    alignas(16) int8_t k[BC * D];    // K_j, row = key, 16-byte chunks XOR-swizzled by row
-    alignas(16) int8_t vt[D * BC];   // V_j^T, row = d, keys in accumulator order, chunks swizzled
-    alignas(16) float sk[BC];        // s_K * log2(e) of the block
+    alignas(1024) int8_t k[2][BC * D];   // K_j, row = key, 16-byte slots XOR-swizzled by row
+    alignas(1024) int8_t v[2][BC * D];   // V_j, row = key, 16-byte slots XOR-swizzled by row
+    alignas(512) float sk[2][BC];        // s_K of the block
 };
 
-// 16-byte chunk c of K row `row` lives at chunk position k_swz(row, c): 8 consecutive rows hit 8
-// different 16-byte slots of a 128-byte line, so a wavefront's 128-bit reads spread over all banks.
-template <int D> __device__ __forceinline__ int k_swz(int row, int c) {
-    return (D == 128) ? (c ^ (row & 7)) : (c ^ ((row >> 1) & 3));
+// Slot swizzles.  Logical 16-byte chunk c of row `row` is stored in slot c ^ swz(row).
+// K is read with ds_read_b128 by 32 consecutive rows at one chunk: 8 consecutive rows must fall in 8
+// different slots of a 128-byte line.  V is read with ds_read_b64_tr_b8, where a 16-lane group touches
+// rows {0-3, 8-11} or {4-7, 12-15} (mod 16) of a tile at one chunk: bits 0, 1 and 3 of the row
+// separate those 8 rows.
+template <int D> __device__ __forceinline__ int k_swz(int row) {
+    return (D == 128) ? (row & 7) : ((row >> 1) & 3);
+}
+template <int D> __device__ __forceinline__ int v_swz(int row) {
+    const int s = (row & 3) | ((row >> 1) & 4);
+    return (D == 128) ? s : (s & 3);
 }
 
-// ---- staging: HBM -> LDS ------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void stage_k(const int8_t *__restrict__ Kh, int j0, int8_t *ks, int tid) {
+// ---- staging: HBM -> LDS, asynchronous ------------------------------------------------------------
+// One global_load_lds_dwordx4 moves 64 x 16 bytes: lane t's 16 bytes land at lds_base + 16 t.  The
+// LDS side is therefore fixed (1 KB contiguous per instruction) and the swizzle is applied on the
+// global side: the lane that fills slot p fetches the chunk that belongs there.
+template <int D, bool IS_V>
+__device__ __forceinline__ void stage_tile_async(const int8_t *__restrict__ gtile, lds_ptr tile, int wave, int lane) {
     constexpr int CH = D / 16;
-    constexpr int ITER = BC * CH / THREADS;
+    constexpr int ITER = BC * CH / THREADS;   // 1 KB pieces per wavefront
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-        const int x = tid + THREADS * i;
-        const int row = x / CH, c = x % CH;
-        const v4i val = *reinterpret_cast<const v4i *>(Kh + static_cast<long>(j0 + row) * D + 16 * c);
-        *reinterpret_cast<v4i *>(ks + row * D + k_swz<D>(row, c) * 16) = val;
+        const int piece = wave * ITER + i;
+        const int p = piece * 64 + lane;
+        const int row = p / CH, slot = p % CH;
+        const int c = slot ^ (IS_V ? v_swz<D>(row) : k_swz<D>(row));
+        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void *)(gtile + row * D + 16 * c),
+                                         reinterpret_cast<LDS_AS void *>(tile + piece * 1024), 16, 0, 0);
     }
 }
 
-// A thread takes 4 consecutive keys x 16 d-bytes, transposes the four 4x4 byte blocks with v_perm
-// and writes 16 dwords, each = 4 consecutive keys of one d column.  Key group kg = key / 4 goes to
-// byte 32*(kg/8) + 16*(kg%2) + 4*((kg%8)/2) of the row: tile kg/8, half g = kg%2, dword (kg%8)/2,
-// which is where accumulator row 8*(v/4) + 4*g + v%4 of that tile puts it.
-template <int D>
-__device__ __forceinline__ void stage_vt(const int8_t *__restrict__ Vh, int j0, int8_t *vt, int tid) {
-    constexpr int CH = D / 16;
-    if (tid < CH * 32) {
-        const int dc = tid % CH, kg = tid / CH;
-        v4i w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = *reinterpret_cast<const v4i *>(Vh + static_cast<long>(j0 + 4 * kg + i) * D + 16 * dc);
-        const int chunk = 2 * (kg >> 3) + (kg & 1);
-        const int within = 4 * ((kg & 7) >> 1);
-#pragma unroll
-        for (int dw = 0; dw < 4; ++dw) {
-            const uint32_t a0 = w[0][dw], a1 = w[1][dw], a2 = w[2][dw], a3 = w[3][dw];
-            const uint32_t t0 = __builtin_amdgcn_perm(a1, a0, 0x05010400u);   // a0.b0 a1.b0 a0.b1 a1.b1
-            const uint32_t t1 = __builtin_amdgcn_perm(a1, a0, 0x07030602u);   // a0.b2 a1.b2 a0.b3 a1.b3
-            const uint32_t t2 = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
-            const uint32_t t3 = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
-            uint32_t o[4];
-            o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);                // byte 0 of a0..a3
-            o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-            o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-            o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int drow = 16 * dc + 4 * dw + c;
-                *reinterpret_cast<uint32_t *>(vt + drow * BC + ((chunk ^ (drow & 7)) * 16) + within) = o[c];
-            }
-        }
-    }
+__device__ __forceinline__ void stage_sk_async(const float *__restrict__ gsk, LDS_AS float *sk, int wave, int lane) {
+    if (wave == 3 && lane < BC / 4)       // 32 lanes x 16 bytes = the 128 scales of the block
+        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void *)(gsk + 4 * lane),
+                                         reinterpret_cast<LDS_AS void *>(sk), 16, 0, 0);
 }
+
+// every outstanding memory operation of this wavefront has completed (vmcnt = expcnt = lgkmcnt = 0)
+__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+
+// Per-lane LDS byte offsets of the MFMA operands inside a K / V tile (tile- and block-independent).
+template <int D> struct LaneOffsets {
+    int k[D / 32];        // A operand of S^T = K Q^T, k-step kk: row r, chunk 2*kk + g   (+ 32*mt*D per key tile)
+    int v[2][D / 32];     // A operand of O^T = V^T P^T: half h (bytes 8h..8h+7), d tile dt (+ 32*mt*D per key tile)
+    int sk;               // first of this lane's s_K values in a 32-key tile (+ 128*mt + 32*vq bytes)
+    __device__ __forceinline__ LaneOffsets(int lane) {
+        const int r = lane & 31, g = lane >> 5;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) k[kk] = r * D + (((2 * kk + g) ^ k_swz<D>(r)) * 16);
+        // transposing read: 16-lane group G = lane / 16 serves d columns 16*(G%2) .. +15 of the tile and key
+        // half g = G / 2; lane i of the group addresses row (i / 2) of its 8 keys, byte half (i % 2).
+        const int i = lane & 15, G = lane >> 4, kidx = i >> 1, par = i & 1;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int b = 8 * h + kidx;
+            const int key = 8 * (b >> 2) + 4 * g + (b & 3);          // accumulator row order
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+                v[h][dt] = key * D + (((2 * dt + (G & 1)) ^ v_swz<D>(key)) * 16) + 8 * par;
+        }
+        sk = 16 * g;
+    }
+};
 
 // ---- the two MFMA tile products -----------------------------------------------------------------
 // S^T tile mt (keys 32*mt .. +31) x this wavefront's 32 queries, contraction over d.
 template <int D>
-__device__ __forceinline__ v16i gemm_kq_tile(const int8_t *ks, const v4i (&qf)[D / 32], int mt, int r, int g) {
+__device__ __forceinline__ v16i gemm_kq_tile(lds_ptr ks, const LaneOffsets<D> &lo, const v4i (&qf)[D / 32], int mt) {
     v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const int row = 32 * mt + r;
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
-        const v4i a = *reinterpret_cast<const v4i *>(ks + row * D + k_swz<D>(row, 2 * kk + g) * 16);
+        const v4i a = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[kk], acc, 0, 0, 0);
     }
     return acc;
 }
 
-// O^T tile dt (d 32*dt .. +31) x 32 queries, contraction over the 128 keys of the block.
-__device__ __forceinline__ v16i gemm_vp_tile(const int8_t *vt, const v4i (&pf)[BC / 32], int dt, int r, int g,
-                                             v16i acc) {
-    const int drow = 32 * dt + r;
-#pragma unroll
-    for (int mt = 0; mt < BC / 32; ++mt) {
-        const v4i a = *reinterpret_cast<const v4i *>(vt + drow * BC + (((2 * mt + g) ^ (drow & 7)) * 16));
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pf[mt], acc, 0, 0, 0);
-    }
-    return acc;
+// one k-step (32 keys of tile mt) of O^T tile dt
+template <int D>
+__device__ __forceinline__ v16i gemm_vp_step(lds_ptr vs, const LaneOffsets<D> &lo, v4i p, int dt, int mt, v16i acc) {
+    const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[0][dt] + 32 * mt * D));
+    const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[1][dt] + 32 * mt * D));
+    const v4i a = {t0[0], t0[1], t1[0], t1[1]};
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, p, acc, 0, 0, 0);
 }
 
 __device__ __forceinline__ float swap32(float x) {   // value held by lane ^ 32
@@ -162,8 +177,82 @@ template <> struct Store4<__hip_bfloat16> {
 };
 
 // ---- the fused kernel ---------------------------------------------------------------------------
+// Online-softmax state of one lane: one query row, half of the keys of every block.
+template <int D> struct RowState {
+    float m2;             // running max in log2 units (identical in lanes r and r + 32)
+    float l;              // running sum of the rounded P over this lane's keys
+    float o[D / 32][16];  // running output, d = 32*dt + 8*(v/4) + 4*g + v%4
+};
+
+// Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: the block on the causal
+// diagonal (query block == key block); keys beyond the query are masked, and 32-key tiles that lie
+// entirely beyond this wavefront's queries are skipped (their P is 0).
+template <int D, bool DIAG>
+__device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, const LDS_AS float *sk, const LaneOffsets<D> &lo,
+                                              const v4i (&qf)[D / 32], float sq2, int wave, int q_local, int g,
+                                              RowState<D> &st) {
+    constexpr int DT = D / 32;
+    // line 9: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
+    float a[4][16];
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        if (DIAG && mt > wave) continue;
+        const v16i s = gemm_kq_tile<D>(ks, lo, qf, mt);
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const v4f sk4 = *reinterpret_cast<const LDS_AS v4f *>(
+                reinterpret_cast<const LDS_AS int8_t *>(sk) + lo.sk + 128 * mt + 32 * vq);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float x = static_cast<float>(s[4 * vq + e]) * sk4[e];
+                if (DIAG && (32 * mt + 8 * vq + 4 * g + e > q_local)) x = -INFINITY;   // masked key
+                a[mt][4 * vq + e] = x;
+                bmax = fmaxf(bmax, x);
+            }
+        }
+    }
+    // line 10
+    bmax = fmaxf(bmax, swap32(bmax));
+    const float m_new = fmaxf(st.m2, bmax * sq2);
+    const float alpha = __builtin_amdgcn_exp2f(st.m2 - m_new);   // exp2(-inf) = 0 on the first block
+    const float mm = m_new - LOG2_R;
+    st.m2 = m_new;
+
+    // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order
+    v4i pf[4];
+    uint32_t psum = 0;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        if (DIAG && mt > wave) continue;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
+            psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
+            pf[mt][vq] = static_cast<int>(w);
+        }
+    }
+    st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
+
+    // line 13
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        v16i pv = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            if (DIAG && mt > wave) continue;
+            pv = gemm_vp_step<D>(vs, lo, pf[mt], dt, mt, pv);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha, static_cast<float>(pv[v]));
+    }
+}
+
 template <int D, bool CAUSAL, typename OutT>
-__global__ __launch_bounds__(THREADS) void int_flash_attn_fwd_kernel(
+__global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
     int heads, int N, OutT *__restrict__ O) {
@@ -188,100 +277,62 @@ __global__ __launch_bounds__(THREADS) void int_flash_attn_fwd_kernel(
     const int8_t *Kh = K + static_cast<long>(head) * N * D;
     const int8_t *Vh = V + static_cast<long>(head) * N * D;
     const float *sKh = sK + static_cast<long>(head) * N;
+    const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
+    const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
+    LDS_AS float *const skbuf = (LDS_AS float *)(&sm.sk[0][0]);
+    const int nblocks = CAUSAL ? (qb + 1) : (N / BC);
+
+    // line 8 for block 0, in flight while Q_i is fetched
+    stage_tile_async<D, false>(Kh, kbuf, wave, lane);
+    stage_tile_async<D, true>(Vh, vbuf, wave, lane);
+    stage_sk_async(sKh, skbuf, wave, lane);
 
     // line 5: Q_i and s_Q,i.  B operand: lane (r, g) holds bytes d = 32*kk + 16*g .. +15 of query r.
     v4i qf[D / 32];
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
         qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
-    const float sq = sQ[qrow];
+    const float sq2 = sQ[qrow] * LOG2E;
+    const LaneOffsets<D> lo(lane);
 
     // line 6
-    float m2 = -INFINITY, l = 0.0f;
-    float o[DT][16];
+    RowState<D> st;
+    st.m2 = -INFINITY;
+    st.l = 0.0f;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[dt][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) st.o[dt][v] = 0.0f;
 
-    const int nblocks = CAUSAL ? (qb + 1) : (N / BC);
+    wait_all_memory();
+    __syncthreads();
+
     for (int jb = 0; jb < nblocks; ++jb) {                       // line 7
-        const int j0 = jb * BC;
-        __syncthreads();                                         // previous block fully consumed
-        stage_k<D>(Kh, j0, sm.k, tid);                           // line 8
-        stage_vt<D>(Vh, j0, sm.vt, tid);
-        if (tid < BC) sm.sk[tid] = sKh[j0 + tid] * LOG2E;
-        __syncthreads();
-
-        // line 9: a = acc * s_K log2e (the positive per-row factor s_Q is applied after the max)
-        float a[4][16];
-        float bmax = -INFINITY;
-        const bool diag = CAUSAL && (jb == qb);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const v16i s = gemm_kq_tile<D>(sm.k, qf, mt, r, g);
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const float4 skv = *reinterpret_cast<const float4 *>(&sm.sk[32 * mt + 8 * vq + 4 * g]);
-                const float sk4[4] = {skv.x, skv.y, skv.z, skv.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float x = static_cast<float>(s[4 * vq + e]) * sk4[e];
-                    if (diag && (32 * mt + 8 * vq + 4 * g + e > q_local)) x = -INFINITY;   // masked key
-                    a[mt][4 * vq + e] = x;
-                    bmax = fmaxf(bmax, x);
-                }
-            }
+        const int cur = jb & 1, nxt = cur ^ 1;
+        if (jb + 1 < nblocks) {                                  // line 8 for the next block, asynchronous
+            const int j1 = (jb + 1) * BC;
+            stage_tile_async<D, false>(Kh + static_cast<long>(j1) * D, kbuf + nxt * BC * D, wave, lane);
+            stage_tile_async<D, true>(Vh + static_cast<long>(j1) * D, vbuf + nxt * BC * D, wave, lane);
+            stage_sk_async(sKh + j1, skbuf + nxt * BC, wave, lane);
         }
-        // line 10
-        bmax = fmaxf(bmax, swap32(bmax));
-        const float m_new = fmaxf(m2, bmax * sq);
-        const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);  // exp2(-inf) = 0 on the first block
-        const float mm = m_new - LOG2_R;
-
-        // line 11: P = rint(127 * 2^(a*s_Q - m_new)), packed 4 keys per dword in accumulator order
-        v4i pf[4];
-        uint32_t psum = 0;
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                uint32_t b[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq, -mm));
-                    b[e] = __float_as_uint(p + RNE_MAGIC);       // low byte = rint(p), 0..127
-                }
-                const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-                const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
-                const uint32_t w = lo | hi;
-                psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
-                pf[mt][vq] = static_cast<int>(w);
-            }
-        }
-        l = __builtin_fmaf(l, alpha, static_cast<float>(psum));                // line 12 (this lane's half of the keys)
-
-        // line 13
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            const v16i pv = gemm_vp_tile(sm.vt, pf, dt, r, g, zero);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[dt][v] = __builtin_fmaf(o[dt][v], alpha, static_cast<float>(pv[v]));
-        }
-        m2 = m_new;
+        if (CAUSAL && jb == qb)
+            process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC, lo, qf, sq2, wave, q_local, g, st);
+        else
+            process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC, lo, qf, sq2, wave, q_local, g, st);
+        wait_all_memory();                                       // my part of the next block has landed in LDS
+        __syncthreads();                                         // everyone's has, and `cur` is free again
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
-    l += swap32(l);
+    const float l = st.l + swap32(st.l);
     const float f = sV[head] / l;
     OutT *orow = O + qrow * D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq)
-            Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, o[dt][4 * vq] * f, o[dt][4 * vq + 1] * f,
-                              o[dt][4 * vq + 2] * f, o[dt][4 * vq + 3] * f);
+            Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
+                              st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
 }
 
 // ---- test hooks: the same tile code, accumulators written out -------------------------------------
@@ -292,15 +343,18 @@ __global__ __launch_bounds__(THREADS) void debug_qk_kernel(const int8_t *__restr
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const long qrow = blockIdx.x * BR + 32 * wave + r;
     const int j0 = blockIdx.y * BC;
+    const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
     v4i qf[D / 32];
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
         qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
-    stage_k<D>(K, j0, sm.k, tid);
+    const LaneOffsets<D> lo(lane);
+    stage_tile_async<D, false>(K + static_cast<long>(j0) * D, kbuf, wave, lane);
+    wait_all_memory();
     __syncthreads();
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-        const v16i s = gemm_kq_tile<D>(sm.k, qf, mt, r, g);
+        const v16i s = gemm_kq_tile<D>(kbuf, lo, qf, mt);
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             S[qrow * N + j0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3)] = s[v];
@@ -314,12 +368,15 @@ __global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restr
     constexpr int DT = D / 32;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const long qrow = blockIdx.x * BR + 32 * wave + r;
+    const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
+    const LaneOffsets<D> lo(lane);
     v16i acc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[dt] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (int j0 = 0; j0 < N; j0 += BC) {
         __syncthreads();
-        stage_vt<D>(V, j0, sm.vt, tid);
+        stage_tile_async<D, true>(V + static_cast<long>(j0) * D, vbuf, wave, lane);
+        wait_all_memory();
         __syncthreads();
         v4i pf[4];                                   // the layout the fused kernel builds in registers
 #pragma unroll
@@ -328,7 +385,9 @@ __global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restr
             for (int vq = 0; vq < 4; ++vq)
                 pf[mt][vq] = *reinterpret_cast<const int *>(P + qrow * N + j0 + 32 * mt + 8 * vq + 4 * g);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) acc[dt] = gemm_vp_tile(sm.vt, pf, dt, r, g, acc[dt]);
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) acc[dt] = gemm_vp_step<D>(vbuf, lo, pf[mt], dt, mt, acc[dt]);
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)

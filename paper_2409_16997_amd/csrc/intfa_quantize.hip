@@ -80,7 +80,7 @@ __device__ __forceinline__ float group_max(float a) {
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__restrict__ X, long rows,
                                                                  int8_t *__restrict__ Xq,
-                                                                 float *__restrict__ scale) {
+                                                                 float *__restrict__ scale, float scale_mul) {
     constexpr int D = LPR * 8;
     constexpr int ROWS_PER_BLOCK = 256 / LPR;
     const int sub = threadIdx.x % LPR;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__r
         const float a = group_max<LPR>(absmax8(x));
         const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
         *reinterpret_cast<uint2 *>(Xq + idx) = quant8(x, inv);
-        if (sub == 0) scale[row] = (a == 0.0f) ? 1.0f : a / 127.0f;
+        if (sub == 0) scale[row] = ((a == 0.0f) ? 1.0f : a / 127.0f) * scale_mul;
     }
 }
 
@@ -153,18 +153,18 @@ __global__ void head_scale_finalize_kernel(float *scale, long heads, int global_
 }
 
 template <typename T>
-int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, hipStream_t st) {
+int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, float scale_mul, hipStream_t st) {
     const int lpr = d / 8;
     const long rows_per_block = 256 / lpr;
     long blocks = (rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 256L * 64) blocks = 256L * 64;          // grid-stride beyond 64 blocks per CU
     const dim3 grid(static_cast<unsigned>(blocks)), block(256);
     switch (lpr) {
-    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4>), grid, block, 0, st, X, rows, Xq, scale); break;
-    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8>), grid, block, 0, st, X, rows, Xq, scale); break;
-    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16>), grid, block, 0, st, X, rows, Xq, scale); break;
-    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32>), grid, block, 0, st, X, rows, Xq, scale); break;
-    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64>), grid, block, 0, st, X, rows, Xq, scale); break;
+    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
     default: return IFA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
@@ -188,19 +188,25 @@ int launch_headwise(const void *X, long heads, long per_head, int8_t *Xq, float 
 
 }  // namespace
 
-extern "C" int quantize_tokenwise(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale) {
+extern "C" int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale,
+                                     float scale_mul, void *hip_stream) {
     if (!X || !Xq || !scale) return IFA_ERR_NULL;
     if (rows <= 0 || d <= 0 || rows > (1L << 40) / d) return IFA_ERR_SHAPE;
     if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 32 && d != 64 && d != 128 && d != 256 && d != 512) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
-    hipStream_t st = ifa_current_stream();
+    if (!(scale_mul > 0.0f) || scale_mul > 3.0e38f) return IFA_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     int8_t *q = reinterpret_cast<int8_t *>(Xq);
     switch (x_dtype) {
-    case IFA_F32: return launch_tokenwise<float>(X, rows, d, q, scale, st);
-    case IFA_F16: return launch_tokenwise<__half>(X, rows, d, q, scale, st);
-    default: return launch_tokenwise<__hip_bfloat16>(X, rows, d, q, scale, st);
+    case IFA_F32: return launch_tokenwise<float>(X, rows, d, q, scale, scale_mul, st);
+    case IFA_F16: return launch_tokenwise<__half>(X, rows, d, q, scale, scale_mul, st);
+    default: return launch_tokenwise<__hip_bfloat16>(X, rows, d, q, scale, scale_mul, st);
     }
+}
+
+extern "C" int quantize_tokenwise(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale) {
+    return quantize_tokenwise_ex(X, x_dtype, rows, d, Xq, scale, 1.0f, ifa_current_stream());
 }
 
 extern "C" int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq,

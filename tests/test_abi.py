@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -71,6 +71,9 @@ def test_argument_validation_happens_on_the_host(L):
     assert q(p, 1, 0, 128, p, p) == -2
     assert q(p, 5, 10, 128, p, p) == -3
     assert q(p, 1, 10, 100, p, p) == -4
+    qx = L.quantize_tokenwise_ex
+    assert qx(p, 1, 10, 128, p, p, 0.0, None) == -2 and qx(p, 1, 10, 128, p, p, float("nan"), None) == -2
+    assert qx(p, 1, 10, 128, null, p, 1.0, None) == -1
     h = L.quantize_headwise
     assert h(p, 1, 4, 128, 64, p, null, 0) == -1
     assert h(p, 1, 0, 128, 64, p, p, 0) == -2

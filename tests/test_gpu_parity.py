@@ -72,6 +72,17 @@ def test_quantize_headwise_bit_exact(ifa, dtype, global_scale):
     assert np.array_equal(s.cpu().numpy().reshape(6).view(np.uint32), ref_s.view(np.uint32))
 
 
+def test_quantize_tokenwise_scale_mul(ifa):
+    # scale_mul multiplies the stored scale once in fp32 and leaves the codes alone
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((300, 128)).astype(np.float16)
+    c = 1.0 / math.sqrt(128)
+    q, s = ifa.quantize_tokenwise(dev(x), scale_mul=c)
+    rq, rs = oracle.quantize_tokenwise(x)
+    assert np.array_equal(q.cpu().numpy(), rq)
+    assert np.array_equal(s.cpu().numpy(), (rs * np.float32(c)).astype(np.float32))
+
+
 def test_quantize_workload_heads_bit_exact(ifa):
     for name in ("c1", "c2", "c4", "c5"):
         w = workloads.WORKLOADS[name]
