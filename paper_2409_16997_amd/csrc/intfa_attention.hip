@@ -88,7 +88,7 @@ __device__ __forceinline__ void stage_tile_async(const int8_t *__restrict__ gtil
     }
 }
 
-__device__ __forceinline__ void stage_sk_async(const float *__restrict__ gsk, LDS_AS float *sk, int wave, int lane) {
+__device__ __forceinline__ void stage_sk_async(const float *__restrict__ gsk, lds_ptr sk, int wave, int lane) {
     if (wave == 3 && lane < BC / 4)       // 32 lanes x 16 bytes = the 128 scales of the block
         __builtin_amdgcn_global_load_lds((const GLOBAL_AS void *)(gsk + 4 * lane),
                                          reinterpret_cast<LDS_AS void *>(sk), 16, 0, 0);
@@ -181,39 +181,104 @@ template <> struct Store4<__hip_bfloat16> {
 template <int D> struct RowState {
     float m2;             // running max in log2 units (identical in lanes r and r + 32)
     float l;              // running sum of the rounded P over this lane's keys
-    float o[D / 32][16];  // running output, d = 32*dt + 8*(v/4) + 4*g + v%4
+    float o[D / 32][16];  // MINUS the running output, d = 32*dt + 8*(v/4) + 4*g + v%4
 };
+
+// max over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
+__device__ __forceinline__ float pair_max(float x) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
 
 // Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: the block on the causal
 // diagonal (query block == key block); keys beyond the query are masked, and 32-key tiles that lie
-// entirely beyond this wavefront's queries are skipped (their P is 0).
+// entirely beyond this wavefront's queries are skipped (their P is 0).  `wave` is wave-uniform.
+//
+// The instruction stream of one wavefront is software-pipelined by hand: LDS operands of the next
+// MFMA group are requested before the current group is issued, and the VALU work on the previous
+// 32-key tile sits between the MFMAs of the current one, so that neither LDS latency nor the
+// MFMA-result latency is exposed.
 template <int D, bool DIAG>
-__device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, const LDS_AS float *sk, const LaneOffsets<D> &lo,
+__device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float sq2, int wave, int q_local, int g,
                                               RowState<D> &st) {
-    constexpr int DT = D / 32;
-    // line 9: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
+    constexpr int KS = D / 32, DT = D / 32;
+    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const int last = DIAG ? wave : 3;                // last active 32-key tile (wave-uniform)
+
+    v4i kop[2][KS];
+    v4f skr[2][4];
     float a[4][16];
     float bmax = -INFINITY;
+
+    auto load_k = [&](int buf, int mt) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        if (DIAG && mt > wave) continue;
-        const v16i s = gemm_kq_tile<D>(ks, lo, qf, mt);
+        for (int kk = 0; kk < KS; ++kk) kop[buf][kk] = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
+    };
+    auto load_sk = [&](int buf, int mt) {
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            const v4f sk4 = *reinterpret_cast<const LDS_AS v4f *>(
-                reinterpret_cast<const LDS_AS int8_t *>(sk) + lo.sk + 128 * mt + 32 * vq);
+        for (int vq = 0; vq < 4; ++vq) skr[buf][vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
+    };
+    // line 9, fp32 part: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
+    auto scale_tile = [&](int mt, const v16i &s, const v4f (&skv)[4]) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float x = static_cast<float>(s[4 * vq + e]) * sk4[e];
+                float x = static_cast<float>(s[4 * vq + e]) * skv[vq][e];
                 if (DIAG && (32 * mt + 8 * vq + 4 * g + e > q_local)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
+    };
+
+    // ---- S^T = K Q^T, tile by tile; tile mt-1 is scaled while tile mt is in the matrix pipe
+    v16i sacc[2];
+    load_k(0, 0);
+    load_sk(0, 0);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        if (mt <= last) {
+            if (mt + 1 <= last) load_k((mt + 1) & 1, mt + 1);
+            sacc[mt & 1] = zero;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt & 1], 0, 0, 0);
+            if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr[(mt - 1) & 1]);
+            __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);           // next tile's LDS reads first
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 40 / KS, 0);  // a share of the previous tile's VALU work
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // the scales of tile mt+1 reuse the registers tile mt-1's scales have just left
+            if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
         }
     }
+    // transposing reads of the first V^T operands go out before the last tile is scaled
+    v4i vop[2][4];
+    auto load_v = [&](int buf, int dt) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            if (mt <= last) {
+                const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[0][dt] + 32 * mt * D));
+                const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[1][dt] + 32 * mt * D));
+                vop[buf][mt] = v4i{t0[0], t0[1], t1[0], t1[1]};
+            }
+        }
+    };
+    load_v(0, 0);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+        if (mt == last) scale_tile(mt, sacc[mt & 1], skr[mt & 1]);
+
     // line 10
-    bmax = fmaxf(bmax, swap32(bmax));
+    bmax = pair_max(bmax);
     const float m_new = fmaxf(st.m2, bmax * sq2);
     const float alpha = __builtin_amdgcn_exp2f(st.m2 - m_new);   // exp2(-inf) = 0 on the first block
     const float mm = m_new - LOG2_R;
@@ -224,31 +289,49 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, const LDS_
     uint32_t psum = 0;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
-        if (DIAG && mt > wave) continue;
+        if (mt <= last) {
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            uint32_t w = 0;
+            for (int vq = 0; vq < 4; ++vq) {
+                uint32_t w = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
-            psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
-            pf[mt][vq] = static_cast<int>(w);
+                for (int e = 0; e < 4; ++e)
+                    w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
+                psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
+                pf[mt][vq] = static_cast<int>(w);
+            }
         }
     }
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
+    __builtin_amdgcn_sched_barrier(0);
 
-    // line 13
+    // line 13: O^T tile by tile; tile dt-1 is folded into O while tile dt is in the matrix pipe
+    v16i pacc[2];
+    // The running output is kept NEGATED: -O' = alpha (-O) - PV.  The negated addend needs the three-address
+    // v_fma_f32, whose result can go back to O's own register; with O = alpha O + PV the compiler picks the
+    // two-address v_fmac_f32, the result lands in the converted-PV register and every element costs a copy.
+    auto fold_o = [&](int dt, const v16i &pv) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha, -static_cast<float>(pv[v]));
+    };
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-        v16i pv = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (dt + 1 < DT) load_v((dt + 1) & 1, dt + 1);
+        pacc[dt & 1] = zero;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            if (DIAG && mt > wave) continue;
-            pv = gemm_vp_step<D>(vs, lo, pf[mt], dt, mt, pv);
+        for (int mt = 0; mt < 4; ++mt)
+            if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
+        if (dt > 0) fold_o(dt - 1, pacc[(dt - 1) & 1]);
+        if (!DIAG) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            }
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha, static_cast<float>(pv[v]));
+        __builtin_amdgcn_sched_barrier(0);
     }
+    fold_o(DT - 1, pacc[(DT - 1) & 1]);
 }
 
 template <int D, bool CAUSAL, typename OutT>
@@ -259,7 +342,8 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int T_r = N / BR;
 
     // Workgroups go round-robin over the 8 XCDs by linear id; keep all query blocks of a head on
@@ -279,7 +363,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const float *sKh = sK + static_cast<long>(head) * N;
     const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
     const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
-    LDS_AS float *const skbuf = (LDS_AS float *)(&sm.sk[0][0]);
+    const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
     const int nblocks = CAUSAL ? (qb + 1) : (N / BC);
 
     // line 8 for block 0, in flight while Q_i is fetched
@@ -307,25 +391,27 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     wait_all_memory();
     __syncthreads();
 
-    for (int jb = 0; jb < nblocks; ++jb) {                       // line 7
+    const int nfull = CAUSAL ? qb : nblocks;                     // blocks strictly below the diagonal
+    for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
         if (jb + 1 < nblocks) {                                  // line 8 for the next block, asynchronous
             const int j1 = (jb + 1) * BC;
             stage_tile_async<D, false>(Kh + static_cast<long>(j1) * D, kbuf + nxt * BC * D, wave, lane);
             stage_tile_async<D, true>(Vh + static_cast<long>(j1) * D, vbuf + nxt * BC * D, wave, lane);
-            stage_sk_async(sKh + j1, skbuf + nxt * BC, wave, lane);
+            stage_sk_async(sKh + j1, skbuf + nxt * BC * 4, wave, lane);
         }
-        if (CAUSAL && jb == qb)
-            process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC, lo, qf, sq2, wave, q_local, g, st);
-        else
-            process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC, lo, qf, sq2, wave, q_local, g, st);
+        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, q_local, g, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
+    }
+    if (CAUSAL) {                                                // the block on the diagonal comes last
+        const int cur = nfull & 1;
+        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, q_local, g, st);
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
     const float l = st.l + swap32(st.l);
-    const float f = sV[head] / l;
+    const float f = -sV[head] / l;                               // st.o holds -O
     OutT *orow = O + qrow * D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
