@@ -29,6 +29,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "intfa.h"
 #include "intfa_internal.h"
@@ -69,6 +70,7 @@ template <int D> __device__ __forceinline__ int v_swz(int row) {
     return (D == 128) ? s : (s & 3);
 }
 
+#if defined(__HIP_DEVICE_COMPILE__)   // device-only code: buffer resources and LDS builtins do not exist in the host pass
 // ---- staging: HBM -> LDS, asynchronous ------------------------------------------------------------
 // One global_load_lds_dwordx4 moves 64 x 16 bytes: lane t's 16 bytes land at lds_base + 16 t.  The
 // LDS side is therefore fixed (1 KB contiguous per instruction) and the swizzle is applied on the
@@ -102,8 +104,17 @@ template <int D> struct LaneOffsets {
     int k[D / 32];        // A operand of S^T = K Q^T, k-step kk: row r, chunk 2*kk + g   (+ 32*mt*D per key tile)
     int v[2][D / 32];     // A operand of O^T = V^T P^T: half h (bytes 8h..8h+7), d tile dt (+ 32*mt*D per key tile)
     int sk;               // first of this lane's s_K values in a 32-key tile (+ 128*mt + 32*vq bytes)
-    __device__ __forceinline__ LaneOffsets(int lane) {
+    unsigned gk[D / 32];  // staging: byte offset inside the K tile in HBM of the chunk this lane moves in piece i
+    unsigned gv[D / 32];  // same for the V tile
+    __device__ __forceinline__ LaneOffsets(int lane, int wave) {
         const int r = lane & 31, g = lane >> 5;
+        constexpr int CH = D / 16, ITER = D / 32;
+#pragma unroll
+        for (int i = 0; i < ITER; ++i) {
+            const int p = (wave * ITER + i) * 64 + lane, row = p / CH, slot = p % CH;
+            gk[i] = row * D + 16 * (slot ^ k_swz<D>(row));
+            gv[i] = row * D + 16 * (slot ^ v_swz<D>(row));
+        }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) k[kk] = r * D + (((2 * kk + g) ^ k_swz<D>(r)) * 16);
         // transposing read: 16-lane group G = lane / 16 serves d columns 16*(G%2) .. +15 of the tile and key
@@ -120,6 +131,40 @@ template <int D> struct LaneOffsets {
         sk = 16 * g;
     }
 };
+
+// What the next key block needs staged.  The copies are buffer_load_dwordx4 ... lds: the tensor's base and
+// size sit in a scalar buffer resource, the block offset in a scalar register and the lane's chunk offset in
+// one loop-invariant VGPR, so a copy costs no vector ALU work, and reads past the tensor return zero instead
+// of faulting.  One "piece" is one such instruction of this wavefront (1 KB); a wavefront moves D/32 pieces of
+// K and of V per block, issued one at a time between MFMA groups so that the four wavefronts of a workgroup do
+// not all queue on the vector-memory port at once.
+struct Prefetch {
+    __amdgpu_buffer_rsrc_t k, v, sk;   // one head's K [N, d], V [N, d] int8 and s_K [N] fp32
+    int koff, skoff;                   // byte offset of the next block inside K (= inside V) and inside s_K
+    lds_ptr lk, lv, lsk;               // LDS destinations (tile bases)
+    bool on;                           // false: nothing follows
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);   // raw, 32-bit data format
+}
+
+template <int D>
+__device__ __forceinline__ void prefetch_k_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
+    if (nx.on)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.k, reinterpret_cast<LDS_AS void *>(nx.lk + (wave * (D / 32) + i) * 1024),
+                                                 16, lo.gk[i], nx.koff, 0, 0);
+}
+template <int D>
+__device__ __forceinline__ void prefetch_v_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
+    if (nx.on)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.v, reinterpret_cast<LDS_AS void *>(nx.lv + (wave * (D / 32) + i) * 1024),
+                                                 16, lo.gv[i], nx.koff, 0, 0);
+}
+__device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int lane) {
+    if (nx.on && wave == 3 && lane < BC / 4)      // 32 lanes x 16 bytes = the 128 scales of the block
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.sk, reinterpret_cast<LDS_AS void *>(nx.lsk), 16, 16 * lane, nx.skoff, 0, 0);
+}
 
 // ---- the two MFMA tile products -----------------------------------------------------------------
 // S^T tile mt (keys 32*mt .. +31) x this wavefront's 32 queries, contraction over d.
@@ -200,8 +245,8 @@ __device__ __forceinline__ float pair_max(float x) {
 // MFMA-result latency is exposed.
 template <int D, bool DIAG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
-                                              const v4i (&qf)[D / 32], float sq2, int wave, int q_local, int g,
-                                              RowState<D> &st) {
+                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int q_local, int g,
+                                              const Prefetch &nx, RowState<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const int last = DIAG ? wave : 3;                // last active 32-key tile (wave-uniform)
@@ -254,6 +299,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             __builtin_amdgcn_sched_barrier(0);
             // the scales of tile mt+1 reuse the registers tile mt-1's scales have just left
             if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
+            if (!DIAG && mt < KS) prefetch_k_piece<D>(nx, lo, wave, mt);
             __builtin_amdgcn_sched_barrier(0);
         } else {
 #pragma unroll
@@ -302,6 +348,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         }
     }
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
+    if (!DIAG) prefetch_sk(nx, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
 
     // line 13: O^T tile by tile; tile dt-1 is folded into O while tile dt is in the matrix pipe
@@ -321,6 +368,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         for (int mt = 0; mt < 4; ++mt)
             if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
         if (dt > 0) fold_o(dt - 1, pacc[(dt - 1) & 1]);
+        if (!DIAG) prefetch_v_piece<D>(nx, lo, wave, dt);
         if (!DIAG) {
             __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
@@ -334,11 +382,14 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     fold_o(DT - 1, pacc[(DT - 1) & 1]);
 }
 
+#endif  // __HIP_DEVICE_COMPILE__
+
 template <int D, bool CAUSAL, typename OutT>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
-    int heads, int N, OutT *__restrict__ O) {
+    int heads, int N, int head_group, OutT *__restrict__ O) {
+#if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
 
@@ -346,13 +397,21 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int T_r = N / BR;
 
-    // Workgroups go round-robin over the 8 XCDs by linear id; keep all query blocks of a head on
-    // one XCD so its K/V stay in that XCD's L2.  Heavy (late) query blocks first under the mask.
+    // Workgroups go round-robin over the 8 XCDs by linear id.  All query blocks of a head run on one XCD,
+    // so its K/V stay in that XCD's L2; an XCD takes its heads `head_group` at a time and, inside a group,
+    // the heavy (late) query blocks of all its heads first, so that under the mask the last workgroups to
+    // start are the light ones.
     int head, qord;
     {
         const int L = blockIdx.x;
-        if ((heads & 7) == 0) { const int s = L >> 3; head = (s / T_r) * 8 + (L & 7); qord = s % T_r; }
-        else { head = L / T_r; qord = L % T_r; }
+        if ((heads & 7) == 0) {
+            const int s = L >> 3, per_group = head_group * T_r;
+            const int grp = s / per_group, t = s % per_group;
+            const int hpx = heads >> 3;                                  // heads per XCD
+            const int gsz = min(head_group, hpx - grp * head_group);     // the last group may be short
+            head = (grp * head_group + t % gsz) * 8 + (L & 7);
+            qord = t / gsz;
+        } else { head = L / T_r; qord = L % T_r; }
     }
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;                           // this lane's query inside the block
@@ -366,10 +425,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
     const int nblocks = CAUSAL ? (qb + 1) : (N / BC);
 
-    // line 8 for block 0, in flight while Q_i is fetched
-    stage_tile_async<D, false>(Kh, kbuf, wave, lane);
-    stage_tile_async<D, true>(Vh, vbuf, wave, lane);
-    stage_sk_async(sKh, skbuf, wave, lane);
+    const __amdgpu_buffer_rsrc_t rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
+    const __amdgpu_buffer_rsrc_t rV = make_rsrc(Vh, static_cast<unsigned>(N) * D);
+    const __amdgpu_buffer_rsrc_t rSK = make_rsrc(sKh, static_cast<unsigned>(N) * 4);
 
     // line 5: Q_i and s_Q,i.  B operand: lane (r, g) holds bytes d = 32*kk + 16*g .. +15 of query r.
     v4i qf[D / 32];
@@ -377,7 +435,13 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     for (int kk = 0; kk < D / 32; ++kk)
         qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
     const float sq2 = sQ[qrow] * LOG2E;
-    const LaneOffsets<D> lo(lane);
+    const LaneOffsets<D> lo(lane, wave);
+    {                                                            // line 8 for block 0
+        const Prefetch first = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, true};
+#pragma unroll
+        for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(first, lo, wave, i); prefetch_v_piece<D>(first, lo, wave, i); }
+        prefetch_sk(first, wave, lane);
+    }
 
     // line 6
     RowState<D> st;
@@ -394,19 +458,17 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int nfull = CAUSAL ? qb : nblocks;                     // blocks strictly below the diagonal
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
-        if (jb + 1 < nblocks) {                                  // line 8 for the next block, asynchronous
-            const int j1 = (jb + 1) * BC;
-            stage_tile_async<D, false>(Kh + static_cast<long>(j1) * D, kbuf + nxt * BC * D, wave, lane);
-            stage_tile_async<D, true>(Vh + static_cast<long>(j1) * D, vbuf + nxt * BC * D, wave, lane);
-            stage_sk_async(sKh + j1, skbuf + nxt * BC * 4, wave, lane);
-        }
-        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, q_local, g, st);
+        const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
+        const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D,
+                             skbuf + nxt * BC * 4, jb + 1 < nblocks};
+        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, q_local, g, pf, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
     if (CAUSAL) {                                                // the block on the diagonal comes last
         const int cur = nfull & 1;
-        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, q_local, g, st);
+        const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
+        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, q_local, g, none, st);
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
@@ -419,12 +481,14 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         for (int vq = 0; vq < 4; ++vq)
             Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
                               st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
+#endif
 }
 
 // ---- test hooks: the same tile code, accumulators written out -------------------------------------
 template <int D>
 __global__ __launch_bounds__(THREADS) void debug_qk_kernel(const int8_t *__restrict__ Q, const int8_t *__restrict__ K,
                                                            int N, int *__restrict__ S) {
+#if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const long qrow = blockIdx.x * BR + 32 * wave + r;
@@ -434,7 +498,7 @@ __global__ __launch_bounds__(THREADS) void debug_qk_kernel(const int8_t *__restr
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
         qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
-    const LaneOffsets<D> lo(lane);
+    const LaneOffsets<D> lo(lane, wave);
     stage_tile_async<D, false>(K + static_cast<long>(j0) * D, kbuf, wave, lane);
     wait_all_memory();
     __syncthreads();
@@ -445,17 +509,19 @@ __global__ __launch_bounds__(THREADS) void debug_qk_kernel(const int8_t *__restr
         for (int v = 0; v < 16; ++v)
             S[qrow * N + j0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3)] = s[v];
     }
+#endif
 }
 
 template <int D>
 __global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restrict__ P, const int8_t *__restrict__ V,
                                                            int N, int *__restrict__ PV) {
+#if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const long qrow = blockIdx.x * BR + 32 * wave + r;
     const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
-    const LaneOffsets<D> lo(lane);
+    const LaneOffsets<D> lo(lane, wave);
     v16i acc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[dt] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -479,17 +545,24 @@ __global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restr
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) PV[qrow * D + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3)] = acc[dt][v];
+#endif
 }
 
 // ---- host side ----------------------------------------------------------------------------------
 hipStream_t g_stream = nullptr;
+
+int head_group_size() {   // experiment knob, to be frozen
+    const char *e = getenv("IFA_HEAD_GROUP");
+    const int v = e ? atoi(e) : 4;
+    return v > 0 ? v : 4;
+}
 
 template <int D, bool CAUSAL, typename OutT>
 int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
                int heads, int N, void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * (N / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, sV, heads, N, static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, sV, heads, N, head_group_size(), static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
