@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--workload", default="c3", help="c1..c5 (default: the headline config, c3)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (known HBM traffic, "
+                         "to calibrate the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the method is a single-device operator; heads shard "
@@ -76,6 +79,13 @@ def main():
     fold = 1.0 / math.sqrt(w.d)                 # softmax scale folded into s_Q (throughput does not depend on it)
     O = torch.empty(sh, dtype=odtype, device=dev)
     torch.cuda.synchronize()
+
+    if args.copy_calibration_mib:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads and writes exactly copy_calibration_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     state = {}
