@@ -238,10 +238,10 @@ __device__ __forceinline__ float pair_max(float x) {
 // diagonal (query block == key block); keys beyond the query are masked, and 32-key tiles that lie
 // entirely beyond this wavefront's queries are skipped (their P is 0).  `wave` is wave-uniform.
 //
-// The instruction stream of one wavefront is software-pipelined by hand: LDS operands of the next
-// MFMA group are requested before the current group is issued, and the VALU work on the previous
-// 32-key tile sits between the MFMAs of the current one, so that neither LDS latency nor the
-// MFMA-result latency is exposed.
+// The source is software-pipelined: LDS operands of the next MFMA group are requested before the
+// current group is issued, and the VALU work on the previous 32-key tile follows the MFMAs of the
+// current one, so that neither LDS latency nor the MFMA-result latency is exposed.  Forcing a finer
+// MFMA/VALU interleave with scheduling barriers measured no better than the compiler's own order.
 template <int D, bool DIAG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float sq2, int wave, int lane, int q_local, int g,
@@ -289,17 +289,9 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             for (int kk = 0; kk < KS; ++kk)
                 sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt & 1], 0, 0, 0);
             if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr[(mt - 1) & 1]);
-            __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);           // next tile's LDS reads first
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 40 / KS, 0);  // a share of the previous tile's VALU work
-            }
-            __builtin_amdgcn_sched_barrier(0);
             // the scales of tile mt+1 reuse the registers tile mt-1's scales have just left
             if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
             if (!DIAG && mt < KS) prefetch_k_piece<D>(nx, lo, wave, mt);
-            __builtin_amdgcn_sched_barrier(0);
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
@@ -348,7 +340,6 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     }
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
     if (!DIAG) prefetch_sk(nx, wave, lane);
-    __builtin_amdgcn_sched_barrier(0);
 
     // line 13: O^T tile by tile; tile dt-1 is folded into O while tile dt is in the matrix pipe
     v16i pacc[2];
@@ -368,15 +359,6 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
         if (dt > 0) fold_o(dt - 1, pacc[(dt - 1) & 1]);
         if (!DIAG) prefetch_v_piece<D>(nx, lo, wave, dt);
-        if (!DIAG) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
     }
     fold_o(DT - 1, pacc[(DT - 1) & 1]);
 }
