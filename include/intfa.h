@@ -88,7 +88,8 @@ int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d,
  *   O                  [B, H, N, d] out, fp16 for int_flash_attn_fwd, o_dtype for the _ex form
  * There is no softmax scale: the paper's S has none.  A caller that wants 1/sqrt(d) multiplies
  * s_Q by it (exact by the linearity remark of Section 3.2).
- * Supported: d in {64, 128}; N a positive multiple of 128; B*H*N*d < 2^40.
+ * Supported: d in {64, 128}; any N >= 1 with N*d < 2^31 (keys at or beyond N are masked in the last,
+ * ragged key block; rows at or beyond N are not written); B*H*N*d < 2^40.
  */
 int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                        const float *s_Q, const float *s_K, const float *s_V,

@@ -161,8 +161,11 @@ __device__ __forceinline__ void prefetch_v_piece(const Prefetch &nx, const LaneO
                                                  16, lo.gv[i], nx.koff, 0, 0);
 }
 __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int lane) {
-    if (nx.on && wave == 3 && lane < BC / 4)      // 32 lanes x 16 bytes = the 128 scales of the block
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.sk, reinterpret_cast<LDS_AS void *>(nx.lsk), 16, 16 * lane, nx.skoff, 0, 0);
+    // 2 x 64 lanes x 4 bytes = the 128 scales of the block, by wavefronts 2 and 3.  Dword copies: a head's
+    // scales start at an arbitrary 4-byte boundary when N is not a multiple of 4.
+    if (nx.on && wave >= 2)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.sk, reinterpret_cast<LDS_AS void *>(nx.lsk + 256 * (wave - 2)), 4,
+                                                 4 * lane + 256 * (wave - 2), nx.skoff, 0, 0);
 }
 
 // ---- the two MFMA tile products -----------------------------------------------------------------
@@ -234,9 +237,11 @@ __device__ __forceinline__ float pair_max(float x) {
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-// Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: the block on the causal
-// diagonal (query block == key block); keys beyond the query are masked, and 32-key tiles that lie
-// entirely beyond this wavefront's queries are skipped (their P is 0).  `wave` is wave-uniform.
+// Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: a block with masked keys --
+// the block on the causal diagonal (query block == key block: keys beyond the query are masked) or the
+// ragged last block (keys at or beyond N are masked).  A key of the block is kept iff its index inside the
+// block is <= klimit (per lane); 32-key tiles after tile `last` (wave-uniform) are masked for every lane of
+// the wavefront and are skipped (their P is 0).  `wave` is wave-uniform.
 //
 // The source is software-pipelined: LDS operands of the next MFMA group are requested before the
 // current group is issued, and the VALU work on the previous 32-key tile follows the MFMAs of the
@@ -244,11 +249,11 @@ __device__ __forceinline__ float pair_max(float x) {
 // MFMA/VALU interleave with scheduling barriers measured no better than the compiler's own order.
 template <int D, bool DIAG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
-                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int q_local, int g,
-                                              const Prefetch &nx, RowState<D> &st) {
+                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile,
+                                              int g, const Prefetch &nx, RowState<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const int last = DIAG ? wave : 3;                // last active 32-key tile (wave-uniform)
+    const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
 
     v4i kop[2][KS];
     v4f skr[2][4];
@@ -270,7 +275,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float x = static_cast<float>(s[4 * vq + e]) * skv[vq][e];
-                if (DIAG && (32 * mt + 8 * vq + 4 * g + e > q_local)) x = -INFINITY;   // masked key
+                if (DIAG && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
@@ -376,7 +381,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-    const int T_r = N / BR;
+    const int T_r = (N + BR - 1) / BR;                           // the last query / key block may be ragged
 
     // Workgroups go round-robin over the 8 XCDs by linear id.  All query blocks of a head run on one XCD,
     // so its K/V stay in that XCD's L2; an XCD takes its heads `head_group` at a time and, inside a group,
@@ -396,7 +401,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     }
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;                           // this lane's query inside the block
-    const long qrow = static_cast<long>(head) * N + qb * BR + q_local;
+    const int q_head = qb * BR + q_local;                        // this lane's query inside the head
+    const bool q_valid = q_head < N;                             // rows past N are computed on a clamped copy, never stored
+    const long qrow = static_cast<long>(head) * N + min(q_head, N - 1);
 
     const int8_t *Kh = K + static_cast<long>(head) * N * D;
     const int8_t *Vh = V + static_cast<long>(head) * N * D;
@@ -404,7 +411,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
     const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
     const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
-    const int nblocks = CAUSAL ? (qb + 1) : (N / BC);
+    const int nblocks = CAUSAL ? (qb + 1) : T_r;                 // B_r == B_c, so T_c == T_r
 
     const __amdgpu_buffer_rsrc_t rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
     const __amdgpu_buffer_rsrc_t rV = make_rsrc(Vh, static_cast<unsigned>(N) * D);
@@ -436,32 +443,41 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     wait_all_memory();
     __syncthreads();
 
-    const int nfull = CAUSAL ? qb : nblocks;                     // blocks strictly below the diagonal
+    const bool ragged = (N % BC) != 0;                           // only the last key block can hold keys >= N
+    const bool masked_last = CAUSAL || ragged;
+    const int nfull = masked_last ? nblocks - 1 : nblocks;       // blocks in which every key counts
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
         const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
         const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D,
                              skbuf + nxt * BC * 4, jb + 1 < nblocks};
-        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, q_local, g, pf, st);
+        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, pf, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
-    if (CAUSAL) {                                                // the block on the diagonal comes last
+    if (masked_last) {   // the block on the causal diagonal, or the ragged last block, comes last
         const int cur = nfull & 1;
         const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
-        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, q_local, g, none, st);
+        // kept keys of this block: index <= query (mask) -- which, for a query < N, also excludes keys >= N -- or
+        // index < N - first key of the block (no mask, ragged N)
+        const int tail = N - 1 - nfull * BC;
+        const int klimit = CAUSAL ? q_local : tail;
+        const int last_tile = CAUSAL ? wave : (tail >> 5);
+        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, last_tile, g, none, st);
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
     const float l = st.l + swap32(st.l);
     const float f = -sV[head] / l;                               // st.o holds -O
     OutT *orow = O + qrow * D;
+    if (q_valid) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq)
-            Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
-                              st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
+            for (int vq = 0; vq < 4; ++vq)
+                Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
+                                  st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
+    }
 #endif
 }
 
@@ -539,7 +555,7 @@ constexpr int HEAD_GROUP = 4;
 template <int D, bool CAUSAL, typename OutT>
 int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
                int heads, int N, void *O, hipStream_t st) {
-    const long wgs = static_cast<long>(heads) * (N / BR);
+    const long wgs = static_cast<long>(heads) * ((N + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
                        st, Q, K, V, sQ, sK, sV, heads, N, HEAD_GROUP, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
@@ -589,8 +605,8 @@ extern "C" int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char 
     const long heads = static_cast<long>(B) * H;
     if (heads > (1L << 40) / N / d) return IFA_ERR_SHAPE;
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
-    if ((d != 64 && d != 128) || N % BR != 0 || N % BC != 0) return IFA_ERR_UNSUPPORTED;
-    if (heads * (N / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
+    if (static_cast<long>(N) * d > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
         (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) ||
         (reinterpret_cast<uintptr_t>(s_V) & 3))

@@ -63,7 +63,7 @@ def test_argument_validation_happens_on_the_host(L):
     assert f(p, p, p, p, p, p, 1, 1, -128, 128, 0, *ok_tail) == -2
     assert f(p, p, p, p, p, p, 1, 1, 128, 128, 0, p, 9, None) == -3
     assert f(p, p, p, p, p, p, 1, 1, 128, 96, 0, *ok_tail) == -4      # head dim not built
-    assert f(p, p, p, p, p, p, 1, 1, 100, 128, 0, *ok_tail) == -4     # ragged N not built
+    assert f(p, p, p, p, p, p, 1, 1, 1 << 30, 128, 0, *ok_tail) == -4  # one head must stay below 2 GiB
     assert f(odd, p, p, p, p, p, 1, 1, 128, 128, 0, *ok_tail) == -4   # misaligned
     assert L.int_flash_attn_fwd(null, p, p, p, p, p, 1, 1, 128, 128, 0, p) == -1
     q = L.quantize_tokenwise

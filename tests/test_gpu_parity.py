@@ -175,6 +175,26 @@ def test_shapes_masks_distributions(ifa, B, H, N, d, causal, dist):
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(1, 128), (37, 64), (127, 128), (129, 128), (200, 64), (333, 128), (1000, 128), (515, 64)])
+def test_ragged_sequence_lengths(ifa, N, d, causal):
+    # N not a multiple of the 128-key block: keys >= N are masked in the last block, rows >= N are not stored
+    w = workloads.custom("t", 1, 3, N, d, causal, dist="normal", seed=N + d)
+    x = quantized_inputs(w, scaled=True)
+    heads = 3
+    sh = (1, heads, N, d)
+    guard = 64                                               # canary rows after O: must stay untouched
+    Obuf = torch.full((heads * N + guard, d), 12345.0, dtype=torch.float32, device="cuda")
+    O = Obuf[:heads * N].view(sh)
+    ifa.int_flash_attn_fwd(dev(x["Qq"].reshape(sh)), dev(x["Kq"].reshape(sh)), dev(x["Vq"].reshape(sh)),
+                           dev(x["sQ"].reshape(1, heads, N)), dev(x["sK"].reshape(1, heads, N)),
+                           dev(x["sV"].reshape(1, heads)), causal=causal, out=O)
+    torch.cuda.synchronize()
+    assert bool((Obuf[heads * N:] == 12345.0).all())
+    check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], causal,
+                         label=f"ragged N={N} d={d} causal={causal}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
 def test_random_int8_grid_inputs_wide_scores(ifa, causal):
     # int8 values over the whole range with score spreads from flat to nearly one-hot rows
     rng = np.random.default_rng(5)
