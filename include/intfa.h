@@ -100,6 +100,28 @@ int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, cons
                           int B, int H, int N, int d, int causal, void *O, int o_dtype,
                           void *hip_stream);
 
+/*
+ * Per-block quantization of V -- the scheme the paper names as its next step (Section 3.2, footnote;
+ * Section 5: "we will use per-block quantization to optimize the implementation of the V matrix").
+ * One scale per (head, block of block_keys consecutive keys) = per V_j of Algorithm 1:
+ *   X [heads, N, d] -> Xq [heads, N, d] int8 (same rounding rule as above),
+ *   scale [heads, ceil(N / block_keys)] fp32 = max|V_j| / 127 (1 for an all-zero block).
+ * Single pass (the block is held in registers).  block_keys * d <= 16384, d a multiple of 8; to feed
+ * int_flash_attn_fwd_vblock, block_keys must equal ifa_block_cols(d, causal).
+ */
+int quantize_blockwise(const void *X, int x_dtype, long heads, long N, int d, int block_keys,
+                       signed char *Xq, float *scale, void *hip_stream);
+
+/*
+ * Algorithm 1 with the per-block V scales above: line 13 becomes O = e^{m_old - m} O + s_V,j (P V_j) and
+ * line 16 divides by l only.  s_Vb is [B, H, ceil(N / ifa_block_cols(d, causal))] fp32, strictly positive.
+ * Everything else as int_flash_attn_fwd_ex.
+ */
+int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                              const float *s_Q, const float *s_K, const float *s_Vb,
+                              int B, int H, int N, int d, int causal, void *O, int o_dtype,
+                              void *hip_stream);
+
 /* B_c of Algorithm 1 as the kernel for (d, causal) uses it; 0 if that pair is unsupported. */
 int ifa_block_cols(int d, int causal);
 

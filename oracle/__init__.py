@@ -40,7 +40,7 @@ def _load():
         lib.orc_qk_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_pv_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
-                                               i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
+                                               i32, i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
         lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
         for f in (lib.orc_quantize_rows, lib.orc_qk_i32, lib.orc_pv_i32,
                   lib.orc_int_flash_attn_fwd, lib.orc_attention_fp64):
@@ -90,6 +90,26 @@ def quantize_headwise(X, global_scale=False):
     return q.reshape(X.shape), s
 
 
+def quantize_blockwise(X, block):
+    """Per-block scheme for V (the paper's stated future work): X [heads, N, d] -> int8 same shape and one scale
+    per (head, block of `block` consecutive keys), shape [heads, ceil(N / block)].  Same rounding rule."""
+    X = np.asarray(X)
+    heads, N, d = X.shape
+    Tc = -(-N // block)
+    q = np.empty(X.shape, np.int8)
+    s = np.empty((heads, Tc), np.float32)
+    full = N // block
+    if full:
+        qq, ss = quantize_rows(X[:, :full * block].reshape(heads * full, block * d))
+        q[:, :full * block] = qq.reshape(heads, full * block, d)
+        s[:, :full] = ss.reshape(heads, full)
+    if full < Tc:
+        qq, ss = quantize_rows(X[:, full * block:].reshape(heads, -1))
+        q[:, full * block:] = qq.reshape(heads, N - full * block, d)
+        s[:, full] = ss
+    return q, s
+
+
 def qk_i32(Q, K):
     Q, K = _c(Q, np.int8), _c(K, np.int8)
     N, d = Q.shape
@@ -108,13 +128,16 @@ def pv_i32(P, V):
 
 def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=None,
                        tie_rel=0.0, tie_abs=0.0, want_P=False):
-    """Algorithm 1.  Q, K, V int8 [heads, N, d]; sQ, sK fp32 [heads, N]; sV fp32 [heads].
+    """Algorithm 1.  Q, K, V int8 [heads, N, d]; sQ, sK fp32 [heads, N]; sV fp32 [heads] (tensor-level scale of V)
+    or [heads, ceil(N/Bc)] (one scale per key block, applied where P V_j enters O).
     Returns a dict: O fp32 [rows, d], l, m fp32 [rows], n_tie int32 [rows], P int8 [rows, N] (if asked)."""
     Q, K, V = _c(Q, np.int8), _c(K, np.int8), _c(V, np.int8)
     heads, N, d = Q.shape
     sQ, sK, sV = _c(sQ, np.float32), _c(sK, np.float32), _c(sV, np.float32)
     assert K.shape == Q.shape and V.shape == Q.shape
-    assert sQ.shape == (heads, N) and sK.shape == (heads, N) and sV.shape == (heads,)
+    sv_per_block = sV.ndim == 2
+    assert sQ.shape == (heads, N) and sK.shape == (heads, N)
+    assert sV.shape == ((heads, -(-N // int(Bc))) if sv_per_block else (heads,))
     if row_idx is not None:
         row_idx = _c(row_idx, np.int64)
         n = row_idx.size
@@ -128,7 +151,7 @@ def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=No
     P = np.empty((n, N), np.int8) if want_P else None
     if n:
         _load().orc_int_flash_attn_fwd(_p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), 1, heads, N, d,
-                                       int(bool(causal)), int(Bc), int(bool(p_quant)),
+                                       int(bool(causal)), int(Bc), int(bool(p_quant)), int(sv_per_block),
                                        _p(row_idx), n, _p(O), _p(l), _p(m),
                                        float(tie_rel), float(tie_abs), _p(n_tie), _p(P))
     return {"O": O, "l": l, "m": m, "n_tie": n_tie, "P": P}

@@ -95,6 +95,10 @@ void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
  * Algorithm 1, one query row at a time (rows are independent, so B_r plays no role).
  *
  *   Q, K, V   int8 [B*H, N, d];  sQ, sK fp32 [B*H, N];  sV fp32 [B*H]
+ *   sv_per_block  0: sV is the tensor-level scalar of Section 3.2, one per head, applied on line 16.
+ *             1: the per-block scheme the paper names as future work (Section 3.2 footnote, Section 5):
+ *             sV is fp32 [B*H, ceil(N/Bc)], one scale per key block V_j, applied where P V_j enters O
+ *             (line 13 becomes O = alpha O + s_V,j (P V_j)) and line 16 divides by l only.
  *   Bc        key-block size: the result depends on it, because block j is rounded on
  *             the grid of the running max after block j, not of the final max.
  *   causal    extension (not in the paper): key index > query index gets S = -inf, P = 0.
@@ -110,12 +114,13 @@ void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
  */
 void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                             const float *sQ, const float *sK, const float *sV,
-                            int B, int H, int64_t N, int d, int causal, int Bc, int p_quant,
+                            int B, int H, int64_t N, int d, int causal, int Bc, int p_quant, int sv_per_block,
                             const int64_t *row_idx, int64_t n_rows,
                             float *O, float *l_out, float *m_out,
                             double tie_rel, double tie_abs, int32_t *n_tie, int8_t *P_out)
 {
     const int64_t total = (int64_t)B * H * N;
+    const int64_t Tc = (N + Bc - 1) / Bc;
     if (row_idx == NULL) n_rows = total;
 
 #pragma omp parallel
@@ -155,6 +160,7 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                     S[jj] = ((float)acc * sq) * skh[j];
                     if (S[jj] > bmax) bmax = S[jj];
                 }
+                const float svj = sv_per_block ? sV[head * Tc + j0 / Bc] : 1.0f;
                 const float m_new = (bmax > m) ? bmax : m;         /* line 10 */
                 const double alpha = (m == -INFINITY) ? 0.0 : exp((double)(m - m_new));
 
@@ -177,7 +183,8 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                     for (int c = 0; c < d; ++c) {                  /* line 13 */
                         int32_t pv = 0;
                         for (int jj = 0; jj < nb; ++jj) pv += P[jj] * (int32_t)Vh[(j0 + jj) * d + c];
-                        o[c] = o[c] * (float)alpha + (float)pv;
+                        o[c] = sv_per_block ? o[c] * (float)alpha + (float)pv * svj
+                                            : o[c] * (float)alpha + (float)pv;
                     }
                 } else {
                     double psum = 0.0;
@@ -189,13 +196,13 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                     for (int c = 0; c < d; ++c) {
                         double pv = 0.0;
                         for (int jj = 0; jj < nb; ++jj) pv += Pr[jj] * (double)Vh[(j0 + jj) * d + c];
-                        od[c] = od[c] * alpha + pv;
+                        od[c] = od[c] * alpha + pv * (double)svj;
                     }
                 }
                 m = m_new;
             }
 
-            const float sv = sV[head];
+            const float sv = sv_per_block ? 1.0f : sV[head];
             if (p_quant) {
                 for (int c = 0; c < d; ++c) O[r * d + c] = (o[c] / l) * sv;   /* line 16 */
                 if (l_out) l_out[r] = l;

@@ -19,6 +19,8 @@ SIGNATURES = {
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
+    "quantize_blockwise": (_i, [_vp, _i, _l, _l, _i, _i, _vp, _vp, _vp]),
+    "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "ifa_block_cols": (_i, [_i, _i]),
     "ifa_debug_qk_i32": (_i, [_vp, _vp, _i, _i, _vp]),
     "ifa_debug_pv_i32": (_i, [_vp, _vp, _i, _i, _vp]),
@@ -108,13 +110,32 @@ def quantize_headwise(X, global_scale=False):
     return Xq, scale
 
 
+def quantize_blockwise(X, block_keys):
+    """X [B, H, N, d] (or [heads, N, d]) -> (int8 same shape, fp32 scale [B, H, ceil(N/block_keys)])."""
+    import torch
+    N, d = X.shape[-2], X.shape[-1]
+    heads = X.numel() // (N * d)
+    Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
+    scale = torch.empty(tuple(X.shape[:-2]) + (-(-N // block_keys),), dtype=torch.float32, device=X.device)
+    _check(lib().quantize_blockwise(_dev(X), _dtype_enum(X), heads, N, d, int(block_keys), _dev(Xq), _dev(scale), _stream()),
+           "quantize_blockwise")
+    return Xq, scale
+
+
 def int_flash_attn_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None):
-    """Algorithm 1 on [B, H, N, d] int8 tensors.  Returns O [B, H, N, d] (fp16 unless out_dtype/out says otherwise)."""
+    """Algorithm 1 on [B, H, N, d] int8 tensors.  Returns O [B, H, N, d] (fp16 unless out_dtype/out says otherwise).
+    s_V [B, H] is the tensor-level scale of V; a 3-d s_V [B, H, ceil(N/B_c)] selects the per-block V scales."""
     import torch
     B, H, N, d = Q_i8.shape
     if out is None:
         out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
-    code = lib().int_flash_attn_fwd_ex(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
+    if s_V.dim() == 3:
+        if s_V.shape != (B, H, -(-N // block_cols(d, causal))):
+            raise IntfaError(f"per-block s_V has shape {tuple(s_V.shape)}")
+        fn = lib().int_flash_attn_fwd_vblock
+    else:
+        fn = lib().int_flash_attn_fwd_ex
+    code = fn(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
                                        _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32),
                                        B, H, N, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
     _check(code, "int_flash_attn_fwd")

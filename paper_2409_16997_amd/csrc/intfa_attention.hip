@@ -247,10 +247,10 @@ __device__ __forceinline__ float pair_max(float x) {
 // current group is issued, and the VALU work on the previous 32-key tile follows the MFMAs of the
 // current one, so that neither LDS latency nor the MFMA-result latency is exposed.  Forcing a finer
 // MFMA/VALU interleave with scheduling barriers measured no better than the compiler's own order.
-template <int D, bool DIAG>
+template <int D, bool DIAG, bool VB>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile,
-                                              int g, const Prefetch &nx, RowState<D> &st) {
+                                              int g, float oscale, const Prefetch &nx, RowState<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
@@ -351,9 +351,12 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     // The running output is kept NEGATED: -O' = alpha (-O) - PV.  The negated addend needs the three-address
     // v_fma_f32, whose result can go back to O's own register; with O = alpha O + PV the compiler picks the
     // two-address v_fmac_f32, the result lands in the converted-PV register and every element costs a copy.
+    // With one V scale per key block the running output is kept in units of the current block's scale:
+    // O/s_j = (alpha s_{j-1}/s_j) (O/s_{j-1}) + P V_j, so the per-block scale costs one scalar multiply per lane.
+    const float alpha_o = VB ? alpha * oscale : alpha;
     auto fold_o = [&](int dt, const v16i &pv) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha, -static_cast<float>(pv[v]));
+        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -static_cast<float>(pv[v]));
     };
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -370,7 +373,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 
 #endif  // __HIP_DEVICE_COMPILE__
 
-template <int D, bool CAUSAL, typename OutT>
+template <int D, bool CAUSAL, bool VB, typename OutT>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
@@ -446,12 +449,18 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const bool ragged = (N % BC) != 0;                           // only the last key block can hold keys >= N
     const bool masked_last = CAUSAL || ragged;
     const int nfull = masked_last ? nblocks - 1 : nblocks;       // blocks in which every key counts
+    // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_r]
+    const float *sVh = VB ? sV + static_cast<long>(head) * T_r : sV + head;
+    float sv_prev = 1.0f;
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
+        const float sv_j = VB ? sVh[jb] : 1.0f;
+        const float oscale = VB ? sv_prev / sv_j : 1.0f;
+        sv_prev = sv_j;
         const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
         const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D,
                              skbuf + nxt * BC * 4, jb + 1 < nblocks};
-        process_block<D, false>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, pf, st);
+        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, oscale, pf, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
@@ -463,12 +472,15 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const int tail = N - 1 - nfull * BC;
         const int klimit = CAUSAL ? q_local : tail;
         const int last_tile = CAUSAL ? wave : (tail >> 5);
-        process_block<D, true>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, last_tile, g, none, st);
+        const float sv_j = VB ? sVh[nfull] : 1.0f;
+        const float oscale = VB ? sv_prev / sv_j : 1.0f;
+        sv_prev = sv_j;
+        process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, last_tile, g, oscale, none, st);
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
     const float l = st.l + swap32(st.l);
-    const float f = -sV[head] / l;                               // st.o holds -O
+    const float f = -(VB ? sv_prev : sVh[0]) / l;                // st.o holds -O (in units of the last block's scale if VB)
     OutT *orow = O + qrow * D;
     if (q_valid) {
 #pragma unroll
@@ -552,23 +564,51 @@ hipStream_t g_stream = nullptr;
 // of 4 gave the shortest causal run of the group sizes 1, 2, 4, 8, 16 measured on MI355X.
 constexpr int HEAD_GROUP = 4;
 
-template <int D, bool CAUSAL, typename OutT>
+template <int D, bool CAUSAL, bool VB, typename OutT>
 int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
                int heads, int N, void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((N + BR - 1) / BR);
-    hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
+    hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, VB, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
                        st, Q, K, V, sQ, sK, sV, heads, N, HEAD_GROUP, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool VB>
 int launch_fwd_dtype(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK,
                      const float *sV, int heads, int N, void *O, int o_dtype, hipStream_t st) {
     switch (o_dtype) {
-    case IFA_F32: return launch_fwd<D, CAUSAL, float>(Q, K, V, sQ, sK, sV, heads, N, O, st);
-    case IFA_F16: return launch_fwd<D, CAUSAL, __half>(Q, K, V, sQ, sK, sV, heads, N, O, st);
-    default: return launch_fwd<D, CAUSAL, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, N, O, st);
+    case IFA_F32: return launch_fwd<D, CAUSAL, VB, float>(Q, K, V, sQ, sK, sV, heads, N, O, st);
+    case IFA_F16: return launch_fwd<D, CAUSAL, VB, __half>(Q, K, V, sQ, sK, sV, heads, N, O, st);
+    default: return launch_fwd<D, CAUSAL, VB, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, N, O, st);
     }
+}
+
+// validation and dispatch shared by the tensor-level and the block-level V scale entry points
+template <bool VB>
+int fwd_entry(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8, const float *s_Q,
+              const float *s_K, const float *s_V, int B, int H, int N, int d, int causal, void *O, int o_dtype,
+              void *hip_stream) {
+    if (!Q_i8 || !K_i8 || !V_i8 || !s_Q || !s_K || !s_V || !O) return IFA_ERR_NULL;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return IFA_ERR_SHAPE;
+    const long heads = static_cast<long>(B) * H;
+    if (heads > (1L << 40) / N / d) return IFA_ERR_SHAPE;
+    if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
+    if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
+    if (static_cast<long>(N) * d > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
+        (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) ||
+        (reinterpret_cast<uintptr_t>(s_V) & 3))
+        return IFA_ERR_UNSUPPORTED;
+    const int8_t *Q = reinterpret_cast<const int8_t *>(Q_i8);
+    const int8_t *K = reinterpret_cast<const int8_t *>(K_i8);
+    const int8_t *V = reinterpret_cast<const int8_t *>(V_i8);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int hd = static_cast<int>(heads);
+    if (d == 128)
+        return causal ? launch_fwd_dtype<128, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
+                      : launch_fwd_dtype<128, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
+    return causal ? launch_fwd_dtype<64, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
+                  : launch_fwd_dtype<64, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
 }
 
 }  // namespace
@@ -600,27 +640,13 @@ extern "C" int ifa_block_cols(int d, int causal) {
 extern "C" int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                                      const float *s_Q, const float *s_K, const float *s_V, int B, int H, int N, int d,
                                      int causal, void *O, int o_dtype, void *hip_stream) {
-    if (!Q_i8 || !K_i8 || !V_i8 || !s_Q || !s_K || !s_V || !O) return IFA_ERR_NULL;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return IFA_ERR_SHAPE;
-    const long heads = static_cast<long>(B) * H;
-    if (heads > (1L << 40) / N / d) return IFA_ERR_SHAPE;
-    if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
-    if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
-    if (static_cast<long>(N) * d > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
-    if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
-        (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) ||
-        (reinterpret_cast<uintptr_t>(s_V) & 3))
-        return IFA_ERR_UNSUPPORTED;
-    const int8_t *Q = reinterpret_cast<const int8_t *>(Q_i8);
-    const int8_t *K = reinterpret_cast<const int8_t *>(K_i8);
-    const int8_t *V = reinterpret_cast<const int8_t *>(V_i8);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const int hd = static_cast<int>(heads);
-    if (d == 128)
-        return causal ? launch_fwd_dtype<128, true>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
-                      : launch_fwd_dtype<128, false>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
-    return causal ? launch_fwd_dtype<64, true>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
-                  : launch_fwd_dtype<64, false>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
+    return fwd_entry<false>(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, N, d, causal, O, o_dtype, hip_stream);
+}
+
+extern "C" int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                         const float *s_Q, const float *s_K, const float *s_Vb, int B, int H, int N,
+                                         int d, int causal, void *O, int o_dtype, void *hip_stream) {
+    return fwd_entry<true>(Q_i8, K_i8, V_i8, s_Q, s_K, s_Vb, B, H, N, d, causal, O, o_dtype, hip_stream);
 }
 
 extern "C" int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,

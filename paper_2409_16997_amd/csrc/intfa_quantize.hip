@@ -137,6 +137,40 @@ __global__ __launch_bounds__(256) void head_quantize_kernel(const void *__restri
     }
 }
 
+// ---- block-level: one scale per (head, block of `block` keys), single pass -----------------------
+// A workgroup owns one block: at most 128 keys x 128 channels = 16384 elements = 8 chunks of 8 per thread,
+// held in registers between the absmax and the rounding, so the activations are read once.
+template <typename T>
+__global__ __launch_bounds__(256) void block_quantize_kernel(const void *__restrict__ X, long N, int d, int block,
+                                                             int8_t *__restrict__ Xq, float *__restrict__ scale) {
+    const long head = blockIdx.y, jb = blockIdx.x;
+    const long first = head * N * d + jb * static_cast<long>(block) * d;     // first element of the block
+    const long keys = (N - jb * block < block) ? (N - jb * block) : block;
+    const int chunks = static_cast<int>(keys * d / 8);
+    float x[8][8];
+    float a = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < chunks) {
+            Load8<T>::get(X, first + 8L * c, x[i]);
+            a = fmaxf(a, absmax8(x[i]));
+        }
+    }
+    a = group_max<64>(a);
+    __shared__ float wmax[4];
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = a;
+    __syncthreads();
+    a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int c = threadIdx.x + 256 * i;
+        if (c < chunks) *reinterpret_cast<uint2 *>(Xq + first + 8L * c) = quant8(x[i], inv);
+    }
+    if (threadIdx.x == 0) scale[head * gridDim.x + jb] = (a == 0.0f) ? 1.0f : a / 127.0f;
+}
+
 __global__ void zero_words_kernel(unsigned *p, long n) {
     const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
@@ -207,6 +241,26 @@ extern "C" int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int 
 
 extern "C" int quantize_tokenwise(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale) {
     return quantize_tokenwise_ex(X, x_dtype, rows, d, Xq, scale, 1.0f, ifa_current_stream());
+}
+
+extern "C" int quantize_blockwise(const void *X, int x_dtype, long heads, long N, int d, int block_keys,
+                                  signed char *Xq, float *scale, void *hip_stream) {
+    if (!X || !Xq || !scale) return IFA_ERR_NULL;
+    if (heads <= 0 || N <= 0 || d <= 0 || block_keys <= 0 || heads > 65535 || N > (1L << 40) / d / heads) return IFA_ERR_SHAPE;
+    if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
+    if (d % 8 != 0 || static_cast<long>(block_keys) * d > 16384) return IFA_ERR_UNSUPPORTED;
+    const long blocks = (N + block_keys - 1) / block_keys;
+    if (blocks > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int8_t *q = reinterpret_cast<int8_t *>(Xq);
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(heads)), block(256);
+    switch (x_dtype) {
+    case IFA_F32: hipLaunchKernelGGL((block_quantize_kernel<float>), grid, block, 0, st, X, N, d, block_keys, q, scale); break;
+    case IFA_F16: hipLaunchKernelGGL((block_quantize_kernel<__half>), grid, block, 0, st, X, N, d, block_keys, q, scale); break;
+    default: hipLaunchKernelGGL((block_quantize_kernel<__hip_bfloat16>), grid, block, 0, st, X, N, d, block_keys, q, scale); break;
+    }
+    return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
 extern "C" int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq,

@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_blockwise", "int_flash_attn_fwd_vblock", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -79,5 +79,10 @@ def test_argument_validation_happens_on_the_host(L):
     assert h(p, 1, 0, 128, 64, p, p, 0) == -2
     assert h(p, 3, 4, 128, 64, p, p, 0) == -3
     assert h(p, 1, 4, 3, 3, p, p, 0) == -4
+    b = L.quantize_blockwise
+    assert b(p, 1, 4, 256, 128, 128, p, null, None) == -1 and b(p, 1, 4, 256, 128, 0, p, p, None) == -2
+    assert b(p, 7, 4, 256, 128, 128, p, p, None) == -3 and b(p, 1, 4, 256, 128, 256, p, p, None) == -4
+    assert L.int_flash_attn_fwd_vblock(p, p, p, p, p, null, 1, 1, 128, 128, 0, p, 1, None) == -1
+    assert L.int_flash_attn_fwd_vblock(p, p, p, p, p, p, 1, 1, 128, 96, 0, p, 1, None) == -4
     assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
     assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1

@@ -276,3 +276,64 @@ def test_row_subset_equals_full():
     rows = np.array([0, 63, 64, 100, 191], np.int64)
     sub = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, True, 16, row_idx=rows)
     assert np.array_equal(sub["O"], full["O"][rows]) and np.array_equal(sub["l"], full["l"][rows])
+
+
+# ---------------------------------------------------------------- per-block V scales (the paper's stated future work)
+
+def test_blockwise_v_quantizer():
+    rng = np.random.default_rng(30)
+    V = rng.standard_normal((3, 200, 16)).astype(np.float32)
+    V[1, 64:128] *= 50.0                                  # one loud block
+    q, s = oracle.quantize_blockwise(V, 64)
+    assert q.shape == V.shape and s.shape == (3, 4)
+    for h in range(3):
+        for jb in range(4):
+            blk = V[h, 64 * jb:64 * (jb + 1)]
+            assert s[h, jb] == np.abs(blk).max() / np.float32(127.0)
+            qb = q[h, 64 * jb:64 * (jb + 1)]
+            assert np.abs(qb).max() == 127
+            assert np.abs(blk - qb.astype(np.float64) * float(s[h, jb])).max() <= 0.5 * s[h, jb] * (1 + 1e-5)
+    # a loud block no longer costs the quiet blocks their resolution
+    qh, sh = oracle.quantize_headwise(V)
+    quiet = slice(128, 200)
+    err_block = np.abs(V[1, quiet] - q[1, quiet] * s[1, 2:4].repeat([64, 8])[:, None]).max()
+    err_head = np.abs(V[1, quiet] - qh[1, quiet] * sh[1]).max()
+    assert err_block < 0.1 * err_head
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_blockwise_v_reduces_to_tensor_level_when_scales_are_equal(causal):
+    rng = np.random.default_rng(31)
+    N, d, Bc = 96, 16, 32
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 2, N, d, score_sigma=1.5)
+    a = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc)
+    b = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, np.repeat(sV[:, None], 3, 1), causal, Bc)
+    assert np.array_equal(a["l"], b["l"]) and np.array_equal(a["m"], b["m"])
+    assert np.allclose(a["O"], b["O"], rtol=2e-6, atol=1e-7 * np.abs(a["O"]).max())
+    # power-of-two scales commute exactly with every fp32 rounding
+    a = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, np.full(2, 0.25, np.float32), causal, Bc)
+    b = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, np.full((2, 3), 0.25, np.float32), causal, Bc)
+    assert np.array_equal(a["O"], b["O"])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_blockwise_v_closed_forms_and_error_bound(causal):
+    rng = np.random.default_rng(32)
+    N, d, Bc = 80, 16, 32                                 # ragged: blocks of 32, 32, 16 keys
+    Qq, Kq, Vq, sQ, sK, _ = random_int8_problem(rng, 2, N, d, score_sigma=1.0)
+    sVb = rng.uniform(0.01, 0.2, (2, 3)).astype(np.float32)
+    Vhat = Vq.astype(np.float64) * np.repeat(sVb.astype(np.float64), Bc, axis=1)[:, :N, None]
+    # uniform scores: O is the (prefix) mean of the block-wise dequantized V
+    Z = np.zeros_like(Qq)
+    out = oracle.int_flash_attn_fwd(Z, Kq, Vq, sQ, sK, sVb, causal, Bc)["O"].reshape(2, N, d)
+    ref = np.cumsum(Vhat, 1) / np.arange(1, N + 1)[None, :, None] if causal else np.broadcast_to(Vhat.mean(1, keepdims=True), (2, N, d))
+    assert np.allclose(out, ref, rtol=2e-6, atol=1e-8)
+    # general scores: p_quant=0 equals fp64 attention of the dequantized inputs, and the P-rounding bound holds
+    ref = oracle.attention_fp64(dequant(Qq, sQ), dequant(Kq, sK), Vhat, causal=causal).reshape(2, N, d)
+    nq = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sVb, causal, Bc, p_quant=False)["O"].reshape(2, N, d)
+    assert np.abs(nq - ref).max() <= 1e-5 * np.abs(ref).max()
+    got = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sVb, causal, Bc)
+    mask = np.tril(np.ones((N, N), bool)) if causal else np.ones((N, N), bool)
+    dev_ = np.abs(Vhat[:, None, :, :] - ref[:, :, None, :]) * mask[None, :, :, None]
+    bound = 0.5 * dev_.sum(2) / got["l"].reshape(2, N, 1)
+    assert np.all(np.abs(got["O"].reshape(2, N, d) - ref) <= bound * (1 + 1e-4) + 1e-6 * np.abs(ref).max())
