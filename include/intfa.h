@@ -61,6 +61,17 @@ int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int d,
                           signed char *Xq, float *scale, float scale_mul, void *hip_stream);
 
 /*
+ * Token-level quantization of the Hadamard-rotated rows (Section 5 names the combination with Hadamard
+ * transformations as future work).  Each row x is replaced by H_d x (Walsh-Hadamard, Sylvester order,
+ * unnormalized, fp32 butterflies in the order h = 1, 2, 4, ...) before the rule of quantize_tokenwise is
+ * applied; the stored scale is max|H_d x| / 127 * scale_mul.  H_d H_d = d I, so rotating the rows of both Q
+ * and K multiplies Q K^T by exactly d: scale_mul = 1/sqrt(d) on both (or 1/d on one) restores S, and the
+ * attention entry points are used unchanged.  Same argument rules as quantize_tokenwise_ex.
+ */
+int quantize_tokenwise_hadamard(const void *X, int x_dtype, long rows, int d,
+                                signed char *Xq, float *scale, float scale_mul, void *hip_stream);
+
+/*
  * Tensor-level symmetric INT8 quantization of V (Section 3.2: S_V = max|V| / R, a single
  * scalar for the head matrix V in R^{N x d}).
  *   X       [heads, N, d] real activations, heads = B*H

@@ -37,6 +37,8 @@ def _load():
         vp, i64, i32, f64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_quantize_rows.argtypes = [vp, i64, i64, vp, vp]
+        lib.orc_hadamard_rows.argtypes = [vp, i64, i64, vp]
+        lib.orc_hadamard_rows.restype = None
         lib.orc_qk_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_pv_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
@@ -76,6 +78,24 @@ def quantize_tokenwise(X):
     X = np.asarray(X)
     q, s = quantize_rows(X.reshape(-1, X.shape[-1]))
     return q.reshape(X.shape), s.reshape(X.shape[:-1])
+
+
+def hadamard_rows(X):
+    """Unnormalized Walsh-Hadamard transform (Sylvester order) of the last axis, fp32 butterflies."""
+    X = np.asarray(X)
+    x2 = _c(X.reshape(-1, X.shape[-1]), np.float32)
+    rows, cols = x2.shape
+    assert cols & (cols - 1) == 0
+    y = np.empty_like(x2)
+    _load().orc_hadamard_rows(_p(x2), rows, cols, _p(y))
+    return y.reshape(X.shape)
+
+
+def quantize_tokenwise_hadamard(X, scale_mul=1.0):
+    """Token-level quantization of the Hadamard-rotated rows: codes of H_d x, scale = max|H_d x| / 127 * scale_mul
+    (scale_mul = 1/sqrt(d) makes the rotation orthonormal)."""
+    q, s = quantize_tokenwise(hadamard_rows(X))
+    return q, (s * np.float32(scale_mul)).astype(np.float32)
 
 
 def quantize_headwise(X, global_scale=False):

@@ -67,6 +67,27 @@ void orc_quantize_rows(const float *X, int64_t rows, int64_t cols, int8_t *q, fl
     }
 }
 
+/* Walsh-Hadamard transform of every row (Sylvester order, unnormalized: H_d H_d = d I), the rotation the paper
+ * names as future work (Section 5: "combine ... with Hadamard transformations").  Applied to the rows of both
+ * Q and K it leaves Q K^T unchanged up to the factor d, and spreads outlier channels over all channels before
+ * the token-level quantization.  The butterflies run in fp32 in the textbook order h = 1, 2, 4, ...:
+ * (x[i], x[i+h]) <- (x[i] + x[i+h], x[i] - x[i+h]) for every i with bit h clear.  cols must be a power of two. */
+void orc_hadamard_rows(const float *X, int64_t rows, int64_t cols, float *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        float *y = Y + r * cols;
+        memcpy(y, X + r * cols, sizeof(float) * (size_t)cols);
+        for (int64_t h = 1; h < cols; h <<= 1)
+            for (int64_t i = 0; i < cols; ++i)
+                if ((i & h) == 0) {
+                    const float a = y[i], b = y[i + h];
+                    y[i] = a + b;
+                    y[i + h] = a - b;
+                }
+    }
+}
+
 /* Algorithm 1 line 9, integer part: S_int[i][j] = sum_k Q[i][k] * K[j][k], one head. */
 void orc_qk_i32(const int8_t *Q, const int8_t *K, int64_t N, int d, int32_t *S)
 {

@@ -16,6 +16,7 @@ SIGNATURES = {
     "ifa_set_stream": (_i, [_vp]),
     "quantize_tokenwise": (_i, [_vp, _i, _l, _i, _vp, _vp]),
     "quantize_tokenwise_ex": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
+    "quantize_tokenwise_hadamard": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
@@ -84,15 +85,16 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def quantize_tokenwise(X, scale_mul=1.0):
-    """X [..., d] fp32/fp16/bf16 on the GPU -> (int8 [..., d], fp32 scale [...] times scale_mul)."""
+def quantize_tokenwise(X, scale_mul=1.0, hadamard=False):
+    """X [..., d] fp32/fp16/bf16 on the GPU -> (int8 [..., d], fp32 scale [...] times scale_mul).
+    hadamard=True quantizes the Walsh-Hadamard transform H_d x of every row instead of x."""
     import torch
     d = X.shape[-1]
     rows = X.numel() // d
     Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
     scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
-    _check(lib().quantize_tokenwise_ex(_dev(X), _dtype_enum(X), rows, d, _dev(Xq), _dev(scale),
-                                       float(scale_mul), _stream()), "quantize_tokenwise")
+    fn = lib().quantize_tokenwise_hadamard if hadamard else lib().quantize_tokenwise_ex
+    _check(fn(_dev(X), _dtype_enum(X), rows, d, _dev(Xq), _dev(scale), float(scale_mul), _stream()), "quantize_tokenwise")
     return Xq, scale
 
 

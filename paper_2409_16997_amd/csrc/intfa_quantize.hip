@@ -76,8 +76,51 @@ __device__ __forceinline__ float group_max(float a) {
     return a;
 }
 
+// value held by lane ^ M (M a power of two < 64): DPP inside a quad, the LDS crossbar (no memory access) beyond
+template <int M> __device__ __forceinline__ float lane_xor(float x) {
+    const int v = __float_as_int(x);
+    if (M == 1) return __int_as_float(__builtin_amdgcn_mov_dpp(v, 0xB1, 0xf, 0xf, true));        // quad_perm [1,0,3,2]
+    if (M == 2) return __int_as_float(__builtin_amdgcn_mov_dpp(v, 0x4E, 0xf, 0xf, true));        // quad_perm [2,3,0,1]
+    if (M == 4) return __int_as_float(__builtin_amdgcn_ds_swizzle(v, 0x101F));                   // bit mode: xor 4
+    if (M == 8) return __int_as_float(__builtin_amdgcn_ds_swizzle(v, 0x201F));
+    if (M == 16) return __int_as_float(__builtin_amdgcn_ds_swizzle(v, 0x401F));
+    return __shfl_xor(x, 32);
+}
+
+// One butterfly stage of the Walsh-Hadamard transform across lanes: elements 8*sub + i and 8*(sub ^ M) + i.
+// The lane with bit M clear holds a and keeps a + b, the other holds b and keeps a - b.
+template <int M, int LPR> __device__ __forceinline__ void hadamard_lane_stage(float (&x)[8], int sub) {
+    if (M < LPR) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float p = lane_xor<M>(x[i]);
+            x[i] = (sub & M) ? (p - x[i]) : (x[i] + p);
+        }
+    }
+}
+
+// Unnormalized Walsh-Hadamard transform (Sylvester order) of a row of 8*LPR elements spread over LPR lanes,
+// stages h = 1, 2, 4 inside the lane's 8 registers, then h = 8, 16, ... across lanes, all in fp32.
+template <int LPR> __device__ __forceinline__ void hadamard_row(float (&x)[8], int sub) {
+#pragma unroll
+    for (int h = 1; h < 8; h <<= 1)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if ((i & h) == 0) {
+                const float a = x[i], b = x[i + h];
+                x[i] = a + b;
+                x[i + h] = a - b;
+            }
+    hadamard_lane_stage<1, LPR>(x, sub);
+    hadamard_lane_stage<2, LPR>(x, sub);
+    hadamard_lane_stage<4, LPR>(x, sub);
+    hadamard_lane_stage<8, LPR>(x, sub);
+    hadamard_lane_stage<16, LPR>(x, sub);
+    hadamard_lane_stage<32, LPR>(x, sub);
+}
+
 // ---- token-level: one row = LPR lanes ---------------------------------------------------------
-template <typename T, int LPR>
+template <typename T, int LPR, bool HADAMARD>
 __global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__restrict__ X, long rows,
                                                                  int8_t *__restrict__ Xq,
                                                                  float *__restrict__ scale, float scale_mul) {
@@ -90,6 +133,7 @@ __global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__r
         float x[8];
         const long idx = row * D + sub * 8;
         Load8<T>::get(X, idx, x);
+        if (HADAMARD) hadamard_row<LPR>(x, sub);
         const float a = group_max<LPR>(absmax8(x));
         const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
         *reinterpret_cast<uint2 *>(Xq + idx) = quant8(x, inv);
@@ -186,7 +230,7 @@ __global__ void head_scale_finalize_kernel(float *scale, long heads, int global_
     }
 }
 
-template <typename T>
+template <typename T, bool HADAMARD>
 int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, float scale_mul, hipStream_t st) {
     const int lpr = d / 8;
     const long rows_per_block = 256 / lpr;
@@ -194,11 +238,11 @@ int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, 
     if (blocks > 256L * 64) blocks = 256L * 64;          // grid-stride beyond 64 blocks per CU
     const dim3 grid(static_cast<unsigned>(blocks)), block(256);
     switch (lpr) {
-    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
     default: return IFA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
@@ -222,8 +266,10 @@ int launch_headwise(const void *X, long heads, long per_head, int8_t *Xq, float 
 
 }  // namespace
 
-extern "C" int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale,
-                                     float scale_mul, void *hip_stream) {
+namespace {
+template <bool HADAMARD>
+int tokenwise_entry(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale, float scale_mul,
+                    void *hip_stream) {
     if (!X || !Xq || !scale) return IFA_ERR_NULL;
     if (rows <= 0 || d <= 0 || rows > (1L << 40) / d) return IFA_ERR_SHAPE;
     if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
@@ -233,10 +279,21 @@ extern "C" int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     int8_t *q = reinterpret_cast<int8_t *>(Xq);
     switch (x_dtype) {
-    case IFA_F32: return launch_tokenwise<float>(X, rows, d, q, scale, scale_mul, st);
-    case IFA_F16: return launch_tokenwise<__half>(X, rows, d, q, scale, scale_mul, st);
-    default: return launch_tokenwise<__hip_bfloat16>(X, rows, d, q, scale, scale_mul, st);
+    case IFA_F32: return launch_tokenwise<float, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
+    case IFA_F16: return launch_tokenwise<__half, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
+    default: return launch_tokenwise<__hip_bfloat16, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
     }
+}
+}  // namespace
+
+extern "C" int quantize_tokenwise_ex(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale,
+                                     float scale_mul, void *hip_stream) {
+    return tokenwise_entry<false>(X, x_dtype, rows, d, Xq, scale, scale_mul, hip_stream);
+}
+
+extern "C" int quantize_tokenwise_hadamard(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale,
+                                           float scale_mul, void *hip_stream) {
+    return tokenwise_entry<true>(X, x_dtype, rows, d, Xq, scale, scale_mul, hip_stream);
 }
 
 extern "C" int quantize_tokenwise(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale) {

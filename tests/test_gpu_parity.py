@@ -83,6 +83,48 @@ def test_quantize_tokenwise_scale_mul(ifa):
     assert np.array_equal(s.cpu().numpy(), (rs * np.float32(c)).astype(np.float32))
 
 
+@pytest.mark.parametrize("dtype", ["float32", "float16", "bfloat16"])
+@pytest.mark.parametrize("rows,d", [(5, 32), (131, 64), (1000, 128), (77, 256), (40, 512)])
+def test_quantize_tokenwise_hadamard_bit_exact(ifa, dtype, rows, d):
+    rng = np.random.default_rng(rows + d)
+    x = rng.standard_normal((rows, d)).astype(np.float32)
+    x[:, rng.choice(d, 3, replace=False)] *= 25.0             # outlier channels, the case the rotation is for
+    x[rows // 2] = 0.0
+    xt = torch.from_numpy(x).to(getattr(torch, dtype)).cuda()
+    c = d ** -0.5
+    q, s = ifa.quantize_tokenwise(xt, scale_mul=c, hadamard=True)
+    rq, rs = oracle.quantize_tokenwise_hadamard(xt.float().cpu().numpy(), c)
+    assert np.array_equal(q.cpu().numpy(), rq)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), rs.view(np.uint32))
+
+
+def test_hadamard_rotated_attention_on_outlier_channels(ifa):
+    # rotate Q and K before quantizing, feed the unchanged attention kernel; parity against the oracle on the
+    # rotated inputs, and accuracy against fp64 attention of the original activations
+    w = workloads.custom("t", 1, 4, 1024, 128, False, dist="uniform_outlier", seed=5)
+    Q, K, V = (workloads.tensor(w, t) for t in "QKV")
+    sh = (1, 4, 1024, 128)
+    d = w.d
+    ref = oracle.attention_fp64(Q, K, V, causal=False, scale=d ** -0.5)
+    Vq, sV = oracle.quantize_headwise(V)
+    res = {}
+    for rot in (False, True):
+        if rot:
+            Qq, sQ = oracle.quantize_tokenwise_hadamard(Q, (d ** -0.5) * (d ** -0.5))   # rotation and softmax scale
+            Kq, sK = oracle.quantize_tokenwise_hadamard(K, d ** -0.5)
+        else:
+            Qq, sQ = oracle.quantize_tokenwise(Q); sQ = (sQ * np.float32(d ** -0.5)).astype(np.float32)
+            Kq, sK = oracle.quantize_tokenwise(K)
+        O = ifa.int_flash_attn_fwd(dev(Qq.reshape(sh)), dev(Kq.reshape(sh)), dev(Vq.reshape(sh)), dev(sQ.reshape(1, 4, -1)),
+                                   dev(sK.reshape(1, 4, -1)), dev(sV.reshape(1, 4)), causal=False, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        O = O.cpu().numpy().reshape(-1, d)
+        check_against_oracle(ifa, O, Qq, Kq, Vq, sQ, sK, sV, False, label=f"outlier channels, hadamard={rot}")
+        res[rot] = np.abs(O - ref).sum() / np.abs(ref).sum()
+    print(f"[MRE outlier channels N=1024] plain {res[False]:.4%}   Hadamard-rotated Q,K {res[True]:.4%}", flush=True)
+    assert res[True] < res[False]
+
+
 def test_quantize_workload_heads_bit_exact(ifa):
     for name in ("c1", "c2", "c4", "c5"):
         w = workloads.WORKLOADS[name]

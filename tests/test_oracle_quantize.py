@@ -85,3 +85,39 @@ def test_monotone_and_idempotent(d):
     # order preserving within a row
     i = np.argsort(x, axis=1)
     assert np.all(np.diff(np.take_along_axis(q.astype(np.int32), i, axis=1), axis=1) >= 0)
+
+
+# ---------------------------------------------------------------- Hadamard rotation (the paper's stated future work)
+
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_hadamard_matches_the_library_matrix_and_is_an_involution(d):
+    import scipy.linalg
+    rng = np.random.default_rng(40)
+    x = rng.integers(-100, 101, (50, d)).astype(np.float32)        # small integers: every butterfly is exact
+    y = oracle.hadamard_rows(x)
+    H = scipy.linalg.hadamard(d).astype(np.float64)
+    assert np.array_equal(y.astype(np.float64), x.astype(np.float64) @ H)
+    assert np.array_equal(oracle.hadamard_rows(y), x * d)           # H H = d I
+    xr = rng.standard_normal((50, d)).astype(np.float32)
+    assert np.allclose(oracle.hadamard_rows(xr), xr.astype(np.float64) @ H, rtol=1e-5, atol=1e-4)
+
+
+def test_hadamard_rotation_leaves_scores_unchanged_and_tames_outlier_channels():
+    rng = np.random.default_rng(41)
+    d = 128
+    Q = rng.integers(-50, 51, (40, d)).astype(np.float32)
+    K = rng.integers(-50, 51, (40, d)).astype(np.float32)
+    S = Q.astype(np.float64) @ K.astype(np.float64).T
+    Sr = oracle.hadamard_rows(Q).astype(np.float64) @ oracle.hadamard_rows(K).astype(np.float64).T
+    assert np.array_equal(Sr, S * d)                                 # (QH)(KH)^T = d QK^T, exactly on integers
+    # outlier channels: quantization error of the scores drops once the rotation spreads them out
+    X = (rng.random((256, d)) - 0.5).astype(np.float32)
+    Y = (rng.random((256, d)) - 0.5).astype(np.float32)
+    X[:, [3, 17, 90, 101]] *= 20; Y[:, [5, 17, 64, 120]] *= 20
+    S = X.astype(np.float64) @ Y.astype(np.float64).T
+    def scores(qf):
+        (qx, sx), (qy, sy) = qf(X), qf(Y)
+        return (qx.astype(np.float64) * sx[:, None]) @ (qy.astype(np.float64) * sy[:, None]).T
+    e_plain = np.abs(scores(oracle.quantize_tokenwise) - S).mean()
+    e_rot = np.abs(scores(lambda a: oracle.quantize_tokenwise_hadamard(a, d ** -0.5)) - S).mean()
+    assert e_rot < 0.5 * e_plain
