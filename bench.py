@@ -146,7 +146,7 @@ def main():
         import oracle
         from oracle import baselines
         # ---- oracle timed on the host cores on a bounded sample: whole heads of the same workload
-        n_heads = {"c1": 1, "c2": 64, "c3": 32, "c4": 2, "c5": 2}[w.name]
+        n_heads = {"c1": 1, "c2": 64, "c3": 128, "c4": 24, "c5": 12}[w.name]   # about 4-6 s of oracle time on 16 cores
         t_cpu = 0.0
         worst = 0.0
         for h in range(n_heads):
