@@ -135,37 +135,62 @@ template <int D> struct LaneOffsets {
 // size sit in a scalar buffer resource, the block offset in a scalar register and the lane's chunk offset in
 // one loop-invariant VGPR, so a copy costs no vector ALU work, and reads past the tensor return zero instead
 // of faulting.  One "piece" is one such instruction of this wavefront (1 KB); a wavefront moves D/32 pieces of
-// K and of V per block, issued one at a time between MFMA groups so that the four wavefronts of a workgroup do
-// not all queue on the vector-memory port at once.
+// K and of V per block, issued one pair at a time between the MFMA groups of S^T so that the four wavefronts
+// of a workgroup do not all queue on the vector-memory port at once and every copy has the rest of the block
+// to land.
+//
+// The copies are written as inline assembly on purpose.  Issued through the compiler's builtin they count as
+// stores to LDS that any later transposing LDS read might alias, and the compiler then waits for ALL of them
+// (vmcnt(0)) in front of the first V^T operand read of the block, which exposes the HBM latency in the middle
+// of every block.  They cannot alias: the copies fill the other half of the double buffer, and the wait that
+// does order them (wait_all_memory + barrier at the end of the block) is explicit.  M0 holds the LDS
+// destination of such a copy; nothing else in this kernel uses M0.
+struct BufRsrc { int w[4]; };        // raw buffer resource: base, base hi (stride 0), bytes, flags
 struct Prefetch {
-    __amdgpu_buffer_rsrc_t k, v, sk;   // one head's K [N, d], V [N, d] int8 and s_K [N] fp32
-    int koff, skoff;                   // byte offset of the next block inside K (= inside V) and inside s_K
-    lds_ptr lk, lv, lsk;               // LDS destinations (tile bases)
-    bool on;                           // false: nothing follows
+    BufRsrc k, v, sk;                // one head's K [N, d], V [N, d] int8 and s_K [N] fp32
+    int koff, skoff;                 // byte offset of the next block inside K (= inside V) and inside s_K
+    lds_ptr lk, lv, lsk;             // LDS destinations (tile bases)
+    bool on;                         // false: nothing follows
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);   // raw, 32-bit data format
+__device__ __forceinline__ BufRsrc make_rsrc(const void *base, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    BufRsrc r;                       // wave-uniform by construction; readfirstlane pins the words to SGPRs
+    r.w[0] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a)));
+    r.w[1] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a >> 32) & 0xffffu));
+    r.w[2] = __builtin_amdgcn_readfirstlane(static_cast<int>(bytes));
+    r.w[3] = 0x00020000;             // raw, 32-bit data format
+    return r;
 }
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// 64 lanes x 16 bytes: lane t's bytes [voff, voff + 16) past soff land at LDS address lds + 16 t
+__device__ __forceinline__ void lds_copy16(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
+    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
+}
+// 64 lanes x 4 bytes, lane t's dword lands at lds + 4 t
+__device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
+    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
+}
+#pragma clang diagnostic pop
 
 template <int D>
 __device__ __forceinline__ void prefetch_k_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.k, reinterpret_cast<LDS_AS void *>(nx.lk + (wave * (D / 32) + i) * 1024),
-                                                 16, lo.gk[i], nx.koff, 0, 0);
+    if (nx.on) lds_copy16(nx.k, nx.lk + (wave * (D / 32) + i) * 1024, lo.gk[i], nx.koff);
 }
 template <int D>
 __device__ __forceinline__ void prefetch_v_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.v, reinterpret_cast<LDS_AS void *>(nx.lv + (wave * (D / 32) + i) * 1024),
-                                                 16, lo.gv[i], nx.koff, 0, 0);
+    if (nx.on) lds_copy16(nx.v, nx.lv + (wave * (D / 32) + i) * 1024, lo.gv[i], nx.koff);
 }
 __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int lane) {
     // 2 x 64 lanes x 4 bytes = the 128 scales of the block, by wavefronts 2 and 3.  Dword copies: a head's
     // scales start at an arbitrary 4-byte boundary when N is not a multiple of 4.
-    if (nx.on && wave >= 2)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(nx.sk, reinterpret_cast<LDS_AS void *>(nx.lsk + 256 * (wave - 2)), 4,
-                                                 4 * lane + 256 * (wave - 2), nx.skoff, 0, 0);
+    if (nx.on && wave >= 2) lds_copy4(nx.sk, nx.lsk + 256 * (wave - 2), 4 * lane + 256 * (wave - 2), nx.skoff);
 }
 
 // ---- the two MFMA tile products -----------------------------------------------------------------
@@ -296,7 +321,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr[(mt - 1) & 1]);
             // the scales of tile mt+1 reuse the registers tile mt-1's scales have just left
             if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
-            if (!DIAG && mt < KS) prefetch_k_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && mt < KS) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
@@ -366,7 +391,6 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         for (int mt = 0; mt < 4; ++mt)
             if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
         if (dt > 0) fold_o(dt - 1, pacc[(dt - 1) & 1]);
-        if (!DIAG) prefetch_v_piece<D>(nx, lo, wave, dt);
     }
     fold_o(DT - 1, pacc[(DT - 1) & 1]);
 }
@@ -416,9 +440,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
     const int nblocks = CAUSAL ? (qb + 1) : T_r;                 // B_r == B_c, so T_c == T_r
 
-    const __amdgpu_buffer_rsrc_t rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
-    const __amdgpu_buffer_rsrc_t rV = make_rsrc(Vh, static_cast<unsigned>(N) * D);
-    const __amdgpu_buffer_rsrc_t rSK = make_rsrc(sKh, static_cast<unsigned>(N) * 4);
+    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
+    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(N) * D);
+    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(N) * 4);
 
     // line 5: Q_i and s_Q,i.  B operand: lane (r, g) holds bytes d = 32*kk + 16*g .. +15 of query r.
     v4i qf[D / 32];
