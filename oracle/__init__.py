@@ -44,6 +44,10 @@ def _load():
         lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
                                                i32, i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
         lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
+        lib.orc_round_to_half.argtypes = [ctypes.c_float]
+        lib.orc_round_to_half.restype = ctypes.c_float
+        lib.orc_int_flash_attn_fwd_half.argtypes = [vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, vp, i64, vp, vp, vp]
+        lib.orc_int_flash_attn_fwd_half.restype = None
         for f in (lib.orc_quantize_rows, lib.orc_qk_i32, lib.orc_pv_i32,
                   lib.orc_int_flash_attn_fwd, lib.orc_attention_fp64):
             f.restype = None
@@ -175,6 +179,37 @@ def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=No
                                        _p(row_idx), n, _p(O), _p(l), _p(m),
                                        float(tie_rel), float(tie_abs), _p(n_tie), _p(P))
     return {"O": O, "l": l, "m": m, "n_tie": n_tie, "P": P}
+
+
+def round_to_half(x):
+    """Nearest fp16 value of each fp32 element (ties to even, gradual underflow), as fp32."""
+    x = _c(x, np.float32)
+    f = _load().orc_round_to_half
+    return np.array([f(float(v)) for v in x.ravel()], np.float32).reshape(x.shape)
+
+
+def int_flash_attn_fwd_half(Q, K, V, sQ, sK, causal, Bc, row_idx=None):
+    """Half-INT8 variant (Section 4): INT8 Q, K with token-level scales, fp16 V, P~ = fp16(exp(S - m)).
+    Q, K int8 [heads, N, d]; V fp16 [heads, N, d]; sQ, sK fp32 [heads, N].  Returns a dict O, l, m."""
+    Q, K = _c(Q, np.int8), _c(K, np.int8)
+    assert V.dtype == np.float16
+    Vf = _c(V, np.float32)                      # exact widening
+    heads, N, d = Q.shape
+    sQ, sK = _c(sQ, np.float32), _c(sK, np.float32)
+    assert K.shape == Q.shape and Vf.shape == Q.shape and sQ.shape == (heads, N) and sK.shape == (heads, N)
+    if row_idx is not None:
+        row_idx = _c(row_idx, np.int64)
+        n = row_idx.size
+        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * N)
+    else:
+        n = heads * N
+    O = np.empty((n, d), np.float32)
+    l = np.empty(n, np.float32)
+    m = np.empty(n, np.float32)
+    if n:
+        _load().orc_int_flash_attn_fwd_half(_p(Q), _p(K), _p(Vf), _p(sQ), _p(sK), 1, heads, N, d,
+                                            int(bool(causal)), int(Bc), _p(row_idx), n, _p(O), _p(l), _p(m))
+    return {"O": O, "l": l, "m": m}
 
 
 def attention_fp64(Q, K, V, causal=False, scale=1.0, row_idx=None):

@@ -13,7 +13,9 @@
  * Pins (tests/test_oracle_*.py): quantizer identity on the int8 grid, half-step error
  * bound, sign symmetry; int32 GEMMs against int64 numpy; p_quant=0 against fp64
  * brute-force attention; single-block closed form; uniform-score and one-hot closed
- * forms; causal prefix properties; scale linearity; the P-rounding error bound.
+ * forms; causal prefix properties; scale linearity; the P-rounding error bound; the fp16
+ * rounding helper against numpy's float16 cast; the half-INT8 variant against fp64 attention of
+ * the dequantized operands within the fp16 rounding bound, and its closed forms.
  * Unpinned: nothing in this file (the MRE magnitudes of Tables 1-2 are context only).
  */
 #include <math.h>
@@ -235,6 +237,106 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
             if (n_tie) n_tie[r] = ties;
         }
         free(S); free(P); free(Pr); free(o); free(od);
+    }
+}
+
+/* Nearest fp16 value of x (round half to even, gradual underflow, overflow to infinity), returned as a float.
+ * Written out on the bit pattern: fp16 has 10 fraction bits, exponents 2^-14 .. 2^15, subnormal step 2^-24. */
+float orc_round_to_half(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    const uint32_t sign = u & 0x80000000u;
+    uint32_t a = u & 0x7fffffffu;
+    float r;
+    if (a >= 0x7f800000u) return x;                               /* inf, nan */
+    if (a >= 0x477ff000u) { a = 0x7f800000u; }                    /* >= 65520 rounds to infinity */
+    else if (a >= 0x38800000u) {                                  /* normal half: drop 13 fraction bits */
+        const uint32_t rem = a & 0x1fffu, lsb = (a >> 13) & 1u;
+        a &= ~0x1fffu;
+        if (rem > 0x1000u || (rem == 0x1000u && lsb)) a += 0x2000u;
+    } else {                                                      /* subnormal half: multiples of 2^-24 */
+        float m;
+        memcpy(&m, &a, 4);
+        m = (float)nearbyint((double)m * 16777216.0) * (1.0f / 16777216.0f);   /* exact: at most 2^10 steps */
+        memcpy(&a, &m, 4);
+    }
+    a |= sign;
+    memcpy(&r, &a, 4);
+    return r;
+}
+
+/*
+ * The half-INT8 variant of Section 4 (INT8 Q and K with token-level scales, FP16 V): Algorithm 1 with the
+ * second GEMM in half precision.  The paper gives one sentence; the reading taken, by analogy with lines 11-13:
+ *   S as in line 9 (int32 product, fp32 scales);  m as in line 10;
+ *   P~ = fp16(exp(S - m))            no factor R, rounded to the nearest fp16 value
+ *   l  = alpha l + rowsum(P~)        the ROUNDED weights, summed in fp32 (as line 12 sums the rounded P)
+ *   O  = alpha O + P~ V_j            fp16 x fp16 products are exact in fp32; fp32 accumulation in key order
+ *   O  = O / l                       no s_V: V is not quantized
+ * Vf holds the caller's fp16 V widened to fp32 [B*H, N, d].  Other arguments as orc_int_flash_attn_fwd.
+ */
+void orc_int_flash_attn_fwd_half(const int8_t *Q, const int8_t *K, const float *Vf,
+                                 const float *sQ, const float *sK,
+                                 int B, int H, int64_t N, int d, int causal, int Bc,
+                                 const int64_t *row_idx, int64_t n_rows,
+                                 float *O, float *l_out, float *m_out)
+{
+    const int64_t total = (int64_t)B * H * N;
+    if (row_idx == NULL) n_rows = total;
+
+#pragma omp parallel
+    {
+        float *S = (float *)malloc(sizeof(float) * (size_t)Bc);
+        float *P = (float *)malloc(sizeof(float) * (size_t)Bc);
+        float *o = (float *)malloc(sizeof(float) * (size_t)d);
+
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t r = 0; r < n_rows; ++r) {
+            const int64_t g = row_idx ? row_idx[r] : r;
+            const int64_t head = g / N, i = g % N;
+            const int8_t *q = Q + g * d;
+            const int8_t *Kh = K + head * N * d;
+            const float *Vh = Vf + head * N * d;
+            const float sq = sQ[g];
+            const float *skh = sK + head * N;
+
+            float m = -INFINITY, l = 0.0f;
+            for (int c = 0; c < d; ++c) o[c] = 0.0f;
+
+            for (int64_t j0 = 0; j0 < N; j0 += Bc) {
+                if (causal && j0 > i) break;
+                const int nb = (int)((N - j0 < Bc) ? (N - j0) : Bc);
+                float bmax = -INFINITY;
+                for (int jj = 0; jj < nb; ++jj) {
+                    const int64_t j = j0 + jj;
+                    if (causal && j > i) { S[jj] = -INFINITY; continue; }
+                    const int8_t *k = Kh + j * d;
+                    int32_t acc = 0;
+                    for (int t = 0; t < d; ++t) acc += (int32_t)q[t] * (int32_t)k[t];
+                    S[jj] = ((float)acc * sq) * skh[j];
+                    if (S[jj] > bmax) bmax = S[jj];
+                }
+                const float m_new = (bmax > m) ? bmax : m;
+                const float alpha = (m == -INFINITY) ? 0.0f : (float)exp((double)(m - m_new));
+                float psum = 0.0f;
+                for (int jj = 0; jj < nb; ++jj) {
+                    P[jj] = (S[jj] == -INFINITY) ? 0.0f : orc_round_to_half((float)exp((double)(S[jj] - m_new)));
+                    psum += P[jj];
+                }
+                l = l * alpha + psum;
+                for (int c = 0; c < d; ++c) {
+                    float pv = 0.0f;
+                    for (int jj = 0; jj < nb; ++jj) pv += P[jj] * Vh[(j0 + jj) * d + c];
+                    o[c] = o[c] * alpha + pv;
+                }
+                m = m_new;
+            }
+            for (int c = 0; c < d; ++c) O[r * d + c] = o[c] / l;
+            if (l_out) l_out[r] = l;
+            if (m_out) m_out[r] = m;
+        }
+        free(S); free(P); free(o);
     }
 }
 
