@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5033.2      # MI355X dense INT8 MFMA: 256 CU x 4 SIMD x 1024 MAC/clk x 2 x 2.4 GHz
+PEAK_F16_TFLOPS = 2516.6    # dense fp16 MFMA: half the INT8 rate
 PREWARM_S = 0.2             # seconds of untimed load before the warm-up steps (clock settling)
 
 
@@ -46,6 +47,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=50,
                     help="untimed steps; the clocks need some tens of steps of load before the step time settles")
     ap.add_argument("--workload", default="c3", help="c1..c5 (default: the headline config, c3)")
+    ap.add_argument("--variant", default="full", choices=["full", "half"],
+                    help="full: Algorithm 1 (INT8 P and V), the headline; half: the half-INT8 variant of Section 4 "
+                         "(INT8 Q, K; fp16 weights and V; V is passed as it is, only Q and K are quantized)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -92,16 +96,25 @@ def main():
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     state = {}
 
+    half = args.variant == "half"
+    if half and w.in_dtype != "float16":
+        sys.exit("bench.py: --variant half needs an fp16 workload (V is consumed as fp16)")
+
     def step(i=None):
         if not args.attn_only or "Qq" not in state:
             Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
             Kq, sK = ifa.quantize_tokenwise(K)
-            Vq, sV = ifa.quantize_headwise(V)
-            state.update(Qq=Qq, Kq=Kq, Vq=Vq, sQ=sQ, sK=sK, sV=sV)
+            state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK)
+            if not half:
+                Vq, sV = ifa.quantize_headwise(V)
+                state.update(Vq=Vq, sV=sV)
         s = state
         if i is not None:
             ev[i][0].record()
-        ifa.int_flash_attn_fwd(s["Qq"], s["Kq"], s["Vq"], s["sQ"], s["sK"], s["sV"], causal=w.causal, out=O)
+        if half:
+            ifa.int_flash_attn_fwd_half(s["Qq"], s["Kq"], V, s["sQ"], s["sK"], causal=w.causal, out=O)
+        else:
+            ifa.int_flash_attn_fwd(s["Qq"], s["Kq"], s["Vq"], s["sQ"], s["sK"], s["sV"], causal=w.causal, out=O)
         if i is not None:
             ev[i][1].record()
 
@@ -134,6 +147,11 @@ def main():
     in_bytes = 2 if w.in_dtype == "float16" else 4
     # algorithmic HBM bytes of the quantize passes: read once (V twice), write one byte, 4 bytes of scale per row
     quant_bytes = elems * (3 * in_bytes + in_bytes + 3) + 4 * (2 * w.heads * w.N + w.heads)
+    if half:                                   # only Q and K are quantized
+        quant_bytes = elems * (2 * in_bytes + 2) + 4 * 2 * w.heads * w.N
+    # roofline peak: both GEMMs on INT8 MFMA, or (half) one on INT8 and one on fp16 MFMA at half the rate
+    peak = PEAK_INT8_TOPS if not half else 2.0 / (1.0 / PEAK_INT8_TOPS + 1.0 / PEAK_F16_TFLOPS)
+    kernel_name = "int_flash_attn_fwd_half_kernel" if half else "int_flash_attn_fwd_kernel"
     quant_ms = max(ms_per_step - attn_ms, 1e-6)
 
     result = {
@@ -141,15 +159,20 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "prewarm_steps": prewarm_steps, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if w.causal else 'non-causal'} "
-                               f"{w.dist} {w.in_dtype} in, {w.out_dtype} out; step = quantize Q,K,V + fused attention",
-                   "block_cols": ifa.block_cols(w.d, w.causal), "softmax_scale": "1/sqrt(d) folded into s_Q",
+                               f"{w.dist} {w.in_dtype} in, {w.out_dtype} out; step = "
+                               + ("quantize Q,K + half-INT8 fused attention (fp16 V)" if half else "quantize Q,K,V + fused attention"),
+                   "variant": args.variant,
+                   "block_cols": ifa.block_cols_half(w.d, w.causal) if half else ifa.block_cols(w.d, w.causal),
+                   "softmax_scale": "1/sqrt(d) folded into s_Q",
                    "ops_per_step": ops},
         "pct_of_int8_mfma_peak": round(100 * tops_step / PEAK_INT8_TOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": "int_flash_attn_fwd_kernel", "achieved": round(tops_attn, 2),
-                     "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s", "frac": round(tops_attn / PEAK_INT8_TOPS, 4),
-                     "traffic": read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
+        "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(tops_attn, 2),
+                     "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(tops_attn / peak, 4),
+                     "traffic": None if half else read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
                      "min_launch_ms": round(attn_ms_min, 4),
-                     "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s"},
+                     "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s"
+                             + ("; half variant: peak is the harmonic mix of the INT8 (first GEMM) and fp16 (second GEMM) "
+                                "MFMA peaks" if half else "")},
         "quantize_pass": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                           "hbm_peak_GBps": 8000.0},
     }
@@ -166,9 +189,12 @@ def main():
             t2 = time.perf_counter()
             Qq, sQ = oracle.quantize_tokenwise(q)
             Kq, sK = oracle.quantize_tokenwise(k)
-            Vq, sV = oracle.quantize_headwise(v)
             sQ = (sQ * np.float32(fold)).astype(np.float32)
-            ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal))
+            if half:
+                ref = oracle.int_flash_attn_fwd_half(Qq, Kq, v, sQ, sK, w.causal, ifa.block_cols_half(w.d, w.causal))
+            else:
+                Vq, sV = oracle.quantize_headwise(v)
+                ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal))
             t_cpu += time.perf_counter() - t2
             if h < 2:                         # the timed oracle output doubles as a parity check of this run
                 b, hh = divmod(h, w.H)
@@ -177,7 +203,8 @@ def main():
         cpu_ops = ops * n_heads / w.heads
         result["cpu_baseline"] = {"value": round(cpu_ops / t_cpu / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
                                   "kind": "oracle", "seconds": round(t_cpu, 2),
-                                  "sample": f"{n_heads} of {w.heads} heads of {w.name} (all rows), quantize + Algorithm 1"}
+                                  "sample": f"{n_heads} of {w.heads} heads of {w.name} (all rows), quantize + "
+                                            + ("half-INT8 variant" if half else "Algorithm 1")}
         result["parity_max_rel_err_vs_oracle"] = worst   # out-dtype rounding included (fp16 output: <= 2^-11 of |O|)
 
         # ---- MRE against fp64 attention of the unquantized activations, beside fp16 and tensor-level FP8
@@ -188,7 +215,7 @@ def main():
         got = O[0, 0].float().cpu().numpy()[rows]
         result["mre_vs_fp64"] = {
             "rows": int(rows.size), "definition": "sum|dO|/sum|O| over sampled rows of head 0",
-            "int8_full (this kernel)": baselines.mre(got, ref64)["sum_ratio"],
+            ("int8_half (this kernel)" if half else "int8_full (this kernel)"): baselines.mre(got, ref64)["sum_ratio"],
             "fp16": baselines.mre(baselines.attention_fp16(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
             "fp8_e4m3_tensor_scale": baselines.mre(baselines.attention_fp8_tensor(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
         }

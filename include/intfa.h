@@ -133,6 +133,23 @@ int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, 
                               int B, int H, int N, int d, int causal, void *O, int o_dtype,
                               void *hip_stream);
 
+/*
+ * Half-INT8 variant (Section 4: "INT8-format Q and K matrices and FP16-format V matrix"): lines 9-10 of
+ * Algorithm 1 as above, then the softmax weights stay real and are rounded to FP16 for the second GEMM:
+ *   P~ = fp16(exp(S - m))  (nearest even, no factor R);   l = e^{m_old - m} l + rowsum(P~)  (the rounded weights, fp32)
+ *   O  = e^{m_old - m} O + P~ V_j  (fp16 x fp16 products, fp32 accumulation);   O = diag(l)^-1 O
+ * over key blocks of ifa_block_cols_half() keys in ascending order.
+ *   Q_i8, K_i8 [B, H, N, d] int8;  s_Q, s_K [B, H, N] fp32, strictly positive;  V_f16 [B, H, N, d] fp16 as the
+ *   caller has it (not quantized, no s_V);  O [B, H, N, d] of o_dtype.
+ * Supported: d in {64, 128}; any N >= 1 with 2*N*d < 2^31.  Same error rules as int_flash_attn_fwd_ex.
+ */
+int int_flash_attn_fwd_half(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
+                            const float *s_Q, const float *s_K,
+                            int B, int H, int N, int d, int causal, void *O, int o_dtype, void *hip_stream);
+
+/* Key-block size of the half-INT8 kernel for (d, causal); 0 if that pair is unsupported. */
+int ifa_block_cols_half(int d, int causal);
+
 /* B_c of Algorithm 1 as the kernel for (d, causal) uses it; 0 if that pair is unsupported. */
 int ifa_block_cols(int d, int causal);
 

@@ -32,22 +32,13 @@
 
 #include "intfa.h"
 #include "intfa_internal.h"
+#include "intfa_device.h"
 
 namespace {
 
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v4f __attribute__((ext_vector_type(4)));
+using namespace ifa_dev;
 
-#define LDS_AS __attribute__((address_space(3)))
-#define GLOBAL_AS __attribute__((address_space(1)))
-typedef LDS_AS int8_t *lds_ptr;
-
-constexpr int BR = 128;       // query rows per workgroup
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
-constexpr int THREADS = 256;  // 4 wavefronts x 32 query rows
-constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
 
 template <int D> struct Smem {
@@ -94,9 +85,6 @@ __device__ __forceinline__ void stage_sk_async(const float *__restrict__ gsk, ld
         __builtin_amdgcn_global_load_lds((const GLOBAL_AS void *)(gsk + 4 * lane),
                                          reinterpret_cast<LDS_AS void *>(sk), 16, 0, 0);
 }
-
-// every outstanding memory operation of this wavefront has completed (vmcnt = expcnt = lgkmcnt = 0)
-__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
 // Per-lane LDS byte offsets of the MFMA operands inside a K / V tile (tile- and block-independent).
 template <int D> struct LaneOffsets {
@@ -145,39 +133,12 @@ template <int D> struct LaneOffsets {
 // of every block.  They cannot alias: the copies fill the other half of the double buffer, and the wait that
 // does order them (wait_all_memory + barrier at the end of the block) is explicit.  M0 holds the LDS
 // destination of such a copy; nothing else in this kernel uses M0.
-struct BufRsrc { int w[4]; };        // raw buffer resource: base, base hi (stride 0), bytes, flags
 struct Prefetch {
     BufRsrc k, v, sk;                // one head's K [N, d], V [N, d] int8 and s_K [N] fp32
     int koff, skoff;                 // byte offset of the next block inside K (= inside V) and inside s_K
     lds_ptr lk, lv, lsk;             // LDS destinations (tile bases)
     bool on;                         // false: nothing follows
 };
-
-__device__ __forceinline__ BufRsrc make_rsrc(const void *base, unsigned bytes) {
-    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    BufRsrc r;                       // wave-uniform by construction; readfirstlane pins the words to SGPRs
-    r.w[0] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a)));
-    r.w[1] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a >> 32) & 0xffffu));
-    r.w[2] = __builtin_amdgcn_readfirstlane(static_cast<int>(bytes));
-    r.w[3] = 0x00020000;             // raw, 32-bit data format
-    return r;
-}
-
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-// 64 lanes x 16 bytes: lane t's bytes [voff, voff + 16) past soff land at LDS address lds + 16 t
-__device__ __forceinline__ void lds_copy16(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
-    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
-}
-// 64 lanes x 4 bytes, lane t's dword lands at lds + 4 t
-__device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
-    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
-}
-#pragma clang diagnostic pop
 
 template <int D>
 __device__ __forceinline__ void prefetch_k_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
@@ -215,39 +176,6 @@ __device__ __forceinline__ v16i gemm_vp_step(lds_ptr vs, const LaneOffsets<D> &l
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, p, acc, 0, 0, 0);
 }
 
-__device__ __forceinline__ float swap32(float x) {   // value held by lane ^ 32
-    return __shfl_xor(x, 32);
-}
-
-// ---- output conversion --------------------------------------------------------------------------
-template <typename T> struct Store4;
-template <> struct Store4<float> {
-    static __device__ __forceinline__ void put(float *p, float a, float b, float c, float d) {
-        *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
-    }
-};
-template <> struct Store4<__half> {
-    static __device__ __forceinline__ void put(__half *p, float a, float b, float c, float d) {
-        __half2 lo = __floats2half2_rn(a, b), hi = __floats2half2_rn(c, d);
-        uint2 w;
-        w.x = *reinterpret_cast<uint32_t *>(&lo);
-        w.y = *reinterpret_cast<uint32_t *>(&hi);
-        *reinterpret_cast<uint2 *>(p) = w;
-    }
-};
-template <> struct Store4<__hip_bfloat16> {
-    static __device__ __forceinline__ uint32_t rne(float x) {   // fp32 -> bf16 bits, round half to even
-        uint32_t u = __float_as_uint(x);
-        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    }
-    static __device__ __forceinline__ void put(__hip_bfloat16 *p, float a, float b, float c, float d) {
-        uint2 w;
-        w.x = rne(a) | (rne(b) << 16);
-        w.y = rne(c) | (rne(d) << 16);
-        *reinterpret_cast<uint2 *>(p) = w;
-    }
-};
-
 // ---- the fused kernel ---------------------------------------------------------------------------
 // Online-softmax state of one lane: one query row, half of the keys of every block.
 template <int D> struct RowState {
@@ -255,12 +183,6 @@ template <int D> struct RowState {
     float l;              // running sum of the rounded P over this lane's keys
     float o[D / 32][16];  // MINUS the running output, d = 32*dt + 8*(v/4) + 4*g + v%4
 };
-
-// max over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
-__device__ __forceinline__ float pair_max(float x) {
-    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-}
 
 // Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: a block with masked keys --
 // the block on the causal diagonal (query block == key block: keys beyond the query are masked) or the
@@ -410,22 +332,8 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int T_r = (N + BR - 1) / BR;                           // the last query / key block may be ragged
 
-    // Workgroups go round-robin over the 8 XCDs by linear id.  All query blocks of a head run on one XCD,
-    // so its K/V stay in that XCD's L2; an XCD takes its heads `head_group` at a time and, inside a group,
-    // the heavy (late) query blocks of all its heads first, so that under the mask the last workgroups to
-    // start are the light ones.
     int head, qord;
-    {
-        const int L = blockIdx.x;
-        if ((heads & 7) == 0) {
-            const int s = L >> 3, per_group = head_group * T_r;
-            const int grp = s / per_group, t = s % per_group;
-            const int hpx = heads >> 3;                                  // heads per XCD
-            const int gsz = min(head_group, hpx - grp * head_group);     // the last group may be short
-            head = (grp * head_group + t % gsz) * 8 + (L & 7);
-            qord = t / gsz;
-        } else { head = L / T_r; qord = L % T_r; }
-    }
+    map_workgroup(blockIdx.x, heads, T_r, head_group, head, qord);
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;                           // this lane's query inside the block
     const int q_head = qb * BR + q_local;                        // this lane's query inside the head
@@ -583,10 +491,6 @@ __global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restr
 
 // ---- host side ----------------------------------------------------------------------------------
 hipStream_t g_stream = nullptr;
-
-// Heads an XCD works on at a time: 4 heads of K and V (N = 4096, d = 128: 4 MB) fit its 4 MB L2, and a group
-// of 4 gave the shortest causal run of the group sizes 1, 2, 4, 8, 16 measured on MI355X.
-constexpr int HEAD_GROUP = 4;
 
 template <int D, bool CAUSAL, bool VB, typename OutT>
 int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,

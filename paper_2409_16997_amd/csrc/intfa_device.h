@@ -1,0 +1,118 @@
+// Device-side helpers shared by the attention kernels of libintfa.so (gfx950 only; not part of the C ABI).
+#ifndef INTFA_DEVICE_H
+#define INTFA_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+namespace ifa_dev {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+#define LDS_AS __attribute__((address_space(3)))
+#define GLOBAL_AS __attribute__((address_space(1)))
+typedef LDS_AS int8_t *lds_ptr;
+
+constexpr int BR = 128;       // query rows per workgroup
+constexpr int THREADS = 256;  // 4 wavefronts x 32 query rows
+constexpr float LOG2E = 1.44269504088896340736f;
+
+// Heads an XCD works on at a time: 4 heads of K and V (N = 4096, d = 128: 4 MB) fit its 4 MB L2, and a group
+// of 4 gave the shortest causal run of the group sizes 1, 2, 4, 8, 16 measured on MI355X.
+constexpr int HEAD_GROUP = 4;
+
+// Workgroups go round-robin over the 8 XCDs by linear id.  All query blocks of a head run on one XCD,
+// so its K/V stay in that XCD's L2; an XCD takes its heads `head_group` at a time and, inside a group,
+// the query blocks of all its heads in the order `qord` = 0, 1, ... (a causal kernel maps qord 0 to the
+// heaviest, i.e. last, query block so that the last workgroups to start are the light ones).
+__device__ __forceinline__ void map_workgroup(int L, int heads, int T_r, int head_group, int &head, int &qord) {
+    if ((heads & 7) == 0) {
+        const int s = L >> 3, per_group = head_group * T_r;
+        const int grp = s / per_group, t = s % per_group;
+        const int hpx = heads >> 3;                                  // heads per XCD
+        const int gsz = min(head_group, hpx - grp * head_group);     // the last group may be short
+        head = (grp * head_group + t % gsz) * 8 + (L & 7);
+        qord = t / gsz;
+    } else { head = L / T_r; qord = L % T_r; }
+}
+
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer resources and LDS builtins do not exist in the host pass
+struct BufRsrc { int w[4]; };        // raw buffer resource: base, base hi (stride 0), bytes, flags
+__device__ __forceinline__ BufRsrc make_rsrc(const void *base, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    BufRsrc r;                       // wave-uniform by construction; readfirstlane pins the words to SGPRs
+    r.w[0] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a)));
+    r.w[1] = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a >> 32) & 0xffffu));
+    r.w[2] = __builtin_amdgcn_readfirstlane(static_cast<int>(bytes));
+    r.w[3] = 0x00020000;             // raw, 32-bit data format
+    return r;
+}
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// 64 lanes x 16 bytes: lane t's bytes [voff, voff + 16) past soff land at LDS address lds + 16 t
+__device__ __forceinline__ void lds_copy16(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
+    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
+}
+// 64 lanes x 4 bytes, lane t's dword lands at lds + 4 t
+__device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
+    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
+}
+#pragma clang diagnostic pop
+
+// every outstanding memory operation of this wavefront has completed (vmcnt = expcnt = lgkmcnt = 0)
+__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+
+// max over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
+__device__ __forceinline__ float pair_max(float x) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+#endif  // __HIP_DEVICE_COMPILE__
+
+__device__ __forceinline__ float swap32(float x) {   // value held by lane ^ 32
+    return __shfl_xor(x, 32);
+}
+
+// ---- output conversion --------------------------------------------------------------------------
+template <typename T> struct Store4;
+template <> struct Store4<float> {
+    static __device__ __forceinline__ void put(float *p, float a, float b, float c, float d) {
+        *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
+    }
+};
+template <> struct Store4<__half> {
+    static __device__ __forceinline__ void put(__half *p, float a, float b, float c, float d) {
+        __half2 lo = __floats2half2_rn(a, b), hi = __floats2half2_rn(c, d);
+        uint2 w;
+        w.x = *reinterpret_cast<uint32_t *>(&lo);
+        w.y = *reinterpret_cast<uint32_t *>(&hi);
+        *reinterpret_cast<uint2 *>(p) = w;
+    }
+};
+template <> struct Store4<__hip_bfloat16> {
+    static __device__ __forceinline__ uint32_t rne(float x) {   // fp32 -> bf16 bits, round half to even
+        uint32_t u = __float_as_uint(x);
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ void put(__hip_bfloat16 *p, float a, float b, float c, float d) {
+        uint2 w;
+        w.x = rne(a) | (rne(b) << 16);
+        w.y = rne(c) | (rne(d) << 16);
+        *reinterpret_cast<uint2 *>(p) = w;
+    }
+};
+
+}  // namespace ifa_dev
+
+#endif  // INTFA_DEVICE_H
