@@ -119,35 +119,72 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
                                                    RowStateH<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = MASKED ? last_tile : NT - 1;
+    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     float a[NT][16];
     float bmax = -INFINITY;
 
-    // ---- S^T = K Q^T and its fp32 scaling, tile by tile
+    // The source is software-pipelined like the INT8 kernel's: LDS operands of the next MFMA group are requested
+    // before the current group is issued, and the vector work on tile t-1 follows the MFMAs of tile t.
+    v4i kop[2][KS];
+    v4f skr[2][4];
+    auto load_k = [&](int buf, int mt) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) kop[buf][kk] = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
+    };
+    auto load_sk = [&](int buf, int mt) {
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) skr[buf][vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + 16 * g + 128 * mt + 32 * vq);
+    };
+    auto scale_tile = [&](int mt, const v16i &acc, const v4f (&skv)[4]) {       // line 9, fp32 part: a = acc * s_K
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float x = static_cast<float>(acc[4 * vq + e]) * skv[vq][e];
+                if (MASKED && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
+                a[mt][4 * vq + e] = x;
+                bmax = fmaxf(bmax, x);
+            }
+    };
+    // V^T operands of d tile dt: one h8 per 16-key step of the active tiles
+    h8 vop[2][2 * NT];
+    auto load_v = [&](int buf, int dt) {
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt)
+            if (mt <= last) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const int koff = (32 * mt + 16 * s) * (2 * D);
+                    const h4 t0 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[0][dt] + koff)));
+                    const h4 t1 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[1][dt] + koff)));
+                    vop[buf][2 * mt + s] = h8{t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
+                }
+            }
+    };
+
+    // ---- S^T = K Q^T, tile by tile
+    v16i sacc[2];
+    load_k(0, 0);
+    load_sk(0, 0);
 #pragma unroll
     for (int mt = 0; mt < NT; ++mt) {
         if (mt <= last) {
-            v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            if (mt + 1 <= last) load_k((mt + 1) & 1, mt + 1);
+            sacc[mt & 1] = zero;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const v4i kop = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop, qf[kk], acc, 0, 0, 0);
-            }
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const v4f skv = *reinterpret_cast<LDS_AS const v4f *>(sk + 16 * g + 128 * mt + 32 * vq);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float x = static_cast<float>(acc[4 * vq + e]) * skv[e];
-                    if (MASKED && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;
-                    a[mt][4 * vq + e] = x;
-                    bmax = fmaxf(bmax, x);
-                }
-            }
+            for (int kk = 0; kk < KS; ++kk)
+                sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt & 1], 0, 0, 0);
+            if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr[(mt - 1) & 1]);
+            if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
         }
     }
+    load_v(0, 0);                                                 // first V^T operands go out before the last tile is scaled
+#pragma unroll
+    for (int mt = 0; mt < NT; ++mt)
+        if (mt == last) scale_tile(mt, sacc[mt & 1], skr[mt & 1]);
 
     bmax = pair_max(bmax);
     const float m_new = fmaxf(st.m2, bmax * sq2);                 // finite from the first block on (key 0 is never masked)
@@ -173,25 +210,20 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
     }
     st.l = __builtin_fmaf(st.l, alpha, psum);
 
-    // ---- O^T = alpha O^T + V^T P~^T: rescale in place, then accumulate with the fp16 MFMA
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) st.o[dt][v] *= alpha;
+    // ---- O^T = alpha O^T + V^T P~^T: each d tile is rescaled in place, then the fp16 MFMAs accumulate onto it
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
+        if (dt + 1 < DT) load_v((dt + 1) & 1, dt + 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st.o[dt][v] *= alpha;
 #pragma unroll
         for (int mt = 0; mt < NT; ++mt) {
             if (mt <= last) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {                       // 16-key steps of the tile
-                    const int koff = (32 * mt + 16 * s) * (2 * D);
-                    const h4 t0 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[0][dt] + koff)));
-                    const h4 t1 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[1][dt] + koff)));
-                    const h8 va = {t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
                     const h8 pb = {ph[mt][4 * s][0], ph[mt][4 * s][1], ph[mt][4 * s + 1][0], ph[mt][4 * s + 1][1],
                                    ph[mt][4 * s + 2][0], ph[mt][4 * s + 2][1], ph[mt][4 * s + 3][0], ph[mt][4 * s + 3][1]};
-                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[dt], 0, 0, 0);
+                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vop[dt & 1][2 * mt + s], pb, st.o[dt], 0, 0, 0);
                 }
             }
         }
@@ -263,24 +295,30 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     if (CAUSAL) nfull = min(nfull, first_q / BCH);               // blocks entirely at or before the first query
     if (N % BCH != 0) nfull = min(nfull, T_c - 1);
     const int wave_last_q = first_q + 32 * wave + 31;            // last query of this wavefront
-    for (int jb = 0; jb < nblocks; ++jb) {
-        const int cur = jb & 1, nxt = cur ^ 1;
-        const int j1 = (jb + 1) * BCH;
-        const PrefetchH nx = {rK, rV, rSK, j1 * D, j1 * D * 2, j1 * 4, kbuf + nxt * BCH * D, vbuf + nxt * BCH * D * 2,
-                              skbuf + nxt * BCH * 4, jb + 1 < nblocks};
-        prefetch_block<D>(nx, lo, wave, lane);
-        const lds_ptr ks = kbuf + cur * BCH * D, vs = vbuf + cur * BCH * D * 2, sks = skbuf + cur * BCH * 4;
-        if (jb < nfull) {
-            process_block_half<D, false>(ks, vs, sks, lo, qf, sq2, 0, NT - 1, g, st);
-        } else {
-            const int j0 = jb * BCH;
-            const int tail = N - 1 - j0;                                           // last valid key of the block
-            const int klimit = CAUSAL ? min(q_head - j0, tail) : tail;             // < 0: nothing kept
-            const int wlim = CAUSAL ? min(wave_last_q - j0, tail) : tail;
-            const int last_tile = wlim < 0 ? -1 : min(NT - 1, wlim >> 5);
-            if (last_tile >= 0)                                                    // wave-uniform
-                process_block_half<D, true>(ks, vs, sks, lo, qf, sq2, klimit, last_tile, g, st);
-        }
+    auto next_block = [&](int jb) {                              // what block jb + 1 needs staged, into the other buffers
+        const int nxt = (jb & 1) ^ 1, j1 = (jb + 1) * BCH;
+        return PrefetchH{rK, rV, rSK, j1 * D, j1 * D * 2, j1 * 4, kbuf + nxt * BCH * D, vbuf + nxt * BCH * D * 2,
+                         skbuf + nxt * BCH * 4, jb + 1 < nblocks};
+    };
+    for (int jb = 0; jb < nfull; ++jb) {
+        const int cur = jb & 1;
+        prefetch_block<D>(next_block(jb), lo, wave, lane);
+        process_block_half<D, false>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
+                                     0, NT - 1, g, st);
+        wait_all_memory();                                       // my part of the next block has landed in LDS
+        __syncthreads();                                         // everyone's has, and `cur` is free again
+    }
+    for (int jb = nfull; jb < nblocks; ++jb) {
+        const int cur = jb & 1;
+        prefetch_block<D>(next_block(jb), lo, wave, lane);
+        const int j0 = jb * BCH;
+        const int tail = N - 1 - j0;                                               // last valid key of the block
+        const int klimit = CAUSAL ? min(q_head - j0, tail) : tail;                 // < 0: nothing kept
+        const int wlim = CAUSAL ? min(wave_last_q - j0, tail) : tail;
+        const int last_tile = wlim < 0 ? -1 : min(NT - 1, wlim >> 5);
+        if (last_tile >= 0)                                                        // wave-uniform
+            process_block_half<D, true>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
+                                        klimit, last_tile, g, st);
         wait_all_memory();
         __syncthreads();
     }
