@@ -41,7 +41,7 @@ def _load():
         lib.orc_hadamard_rows.restype = None
         lib.orc_qk_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_pv_i32.argtypes = [vp, vp, i64, i32, vp]
-        lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
+        lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i64, i32, i32, i32,
                                                i32, i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
         lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
         lib.orc_round_to_half.argtypes = [ctypes.c_float]
@@ -152,29 +152,33 @@ def pv_i32(P, V):
 
 def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=None,
                        tie_rel=0.0, tie_abs=0.0, want_P=False):
-    """Algorithm 1.  Q, K, V int8 [heads, N, d]; sQ, sK fp32 [heads, N]; sV fp32 [heads] (tensor-level scale of V)
-    or [heads, ceil(N/Bc)] (one scale per key block, applied where P V_j enters O).
+    """Algorithm 1.  Q int8 [heads, Nq, d], sQ fp32 [heads, Nq]; K, V int8 [heads, N, d], sK fp32 [heads, N]
+    (Nq = N in the paper; with Nq != N the queries are the last Nq positions for the causal mask);
+    sV fp32 [heads] (tensor-level scale of V) or [heads, ceil(N/Bc)] (one scale per key block, applied where
+    P V_j enters O).
     Returns a dict: O fp32 [rows, d], l, m fp32 [rows], n_tie int32 [rows], P int8 [rows, N] (if asked)."""
     Q, K, V = _c(Q, np.int8), _c(K, np.int8), _c(V, np.int8)
-    heads, N, d = Q.shape
+    heads, Nq, d = Q.shape
+    N = K.shape[1]
     sQ, sK, sV = _c(sQ, np.float32), _c(sK, np.float32), _c(sV, np.float32)
-    assert K.shape == Q.shape and V.shape == Q.shape
+    assert K.shape == (heads, N, d) and V.shape == K.shape
+    assert not causal or N >= Nq
     sv_per_block = sV.ndim == 2
-    assert sQ.shape == (heads, N) and sK.shape == (heads, N)
+    assert sQ.shape == (heads, Nq) and sK.shape == (heads, N)
     assert sV.shape == ((heads, -(-N // int(Bc))) if sv_per_block else (heads,))
     if row_idx is not None:
         row_idx = _c(row_idx, np.int64)
         n = row_idx.size
-        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * N)
+        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * Nq)
     else:
-        n = heads * N
+        n = heads * Nq
     O = np.empty((n, d), np.float32)
     l = np.empty(n, np.float32)
     m = np.empty(n, np.float32)
     n_tie = np.zeros(n, np.int32)
     P = np.empty((n, N), np.int8) if want_P else None
     if n:
-        _load().orc_int_flash_attn_fwd(_p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), 1, heads, N, d,
+        _load().orc_int_flash_attn_fwd(_p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), 1, heads, Nq, N, d,
                                        int(bool(causal)), int(Bc), int(bool(p_quant)), int(sv_per_block),
                                        _p(row_idx), n, _p(O), _p(l), _p(m),
                                        float(tie_rel), float(tie_abs), _p(n_tie), _p(P))

@@ -117,17 +117,20 @@ void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
 /*
  * Algorithm 1, one query row at a time (rows are independent, so B_r plays no role).
  *
- *   Q, K, V   int8 [B*H, N, d];  sQ, sK fp32 [B*H, N];  sV fp32 [B*H]
+ *   Q         int8 [B*H, Nq, d], sQ fp32 [B*H, Nq];  K, V int8 [B*H, N, d], sK fp32 [B*H, N];  sV fp32 [B*H]
+ *             Nq = N is the paper's setting.  Nq != N (a chunk of queries against a longer key sequence) is an
+ *             extension: rows are independent, so nothing else changes.
  *   sv_per_block  0: sV is the tensor-level scalar of Section 3.2, one per head, applied on line 16.
  *             1: the per-block scheme the paper names as future work (Section 3.2 footnote, Section 5):
  *             sV is fp32 [B*H, ceil(N/Bc)], one scale per key block V_j, applied where P V_j enters O
  *             (line 13 becomes O = alpha O + s_V,j (P V_j)) and line 16 divides by l only.
  *   Bc        key-block size: the result depends on it, because block j is rounded on
  *             the grid of the running max after block j, not of the final max.
- *   causal    extension (not in the paper): key index > query index gets S = -inf, P = 0.
+ *   causal    extension (not in the paper): key index > query index + (N - Nq) gets S = -inf, P = 0
+ *             (the queries are the LAST Nq positions of the key sequence; needs N >= Nq).
  *   p_quant   1: Algorithm 1 (P rounded to int8, l sums the rounded P)
  *             0: the FlashAttention-2 recurrence of Section 3.1 (P~ kept real), in fp64
- *   row_idx   global row ids head*N + i to evaluate (NULL: all B*H*N rows in order)
+ *   row_idx   global row ids head*Nq + i to evaluate (NULL: all B*H*N rows in order)
  *   O         fp32 [n_rows, d]
  *   l_out, m_out   optional fp32 [n_rows]: final l and m
  *   n_tie     optional int32 [n_rows]: number of P entries whose rounding would change if
@@ -137,12 +140,13 @@ void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
  */
 void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                             const float *sQ, const float *sK, const float *sV,
-                            int B, int H, int64_t N, int d, int causal, int Bc, int p_quant, int sv_per_block,
+                            int B, int H, int64_t Nq, int64_t N, int d, int causal, int Bc, int p_quant, int sv_per_block,
                             const int64_t *row_idx, int64_t n_rows,
                             float *O, float *l_out, float *m_out,
                             double tie_rel, double tie_abs, int32_t *n_tie, int8_t *P_out)
 {
-    const int64_t total = (int64_t)B * H * N;
+    const int64_t total = (int64_t)B * H * Nq;
+    const int64_t shift = N - Nq;   /* causal: query i sees keys j <= i + shift (the last query sees every key) */
     const int64_t Tc = (N + Bc - 1) / Bc;
     if (row_idx == NULL) n_rows = total;
 
@@ -157,7 +161,7 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
 #pragma omp for schedule(dynamic, 16)
         for (int64_t r = 0; r < n_rows; ++r) {
             const int64_t g = row_idx ? row_idx[r] : r;
-            const int64_t head = g / N, i = g % N;
+            const int64_t head = g / Nq, i = g % Nq + (causal ? shift : 0);   /* i: last visible key if causal */
             const int8_t *q = Q + g * d;
             const int8_t *Kh = K + head * N * d;
             const int8_t *Vh = V + head * N * d;

@@ -337,3 +337,44 @@ def test_blockwise_v_closed_forms_and_error_bound(causal):
     dev_ = np.abs(Vhat[:, None, :, :] - ref[:, :, None, :]) * mask[None, :, :, None]
     bound = 0.5 * dev_.sum(2) / got["l"].reshape(2, N, 1)
     assert np.all(np.abs(got["O"].reshape(2, N, d) - ref) <= bound * (1 + 1e-4) + 1e-6 * np.abs(ref).max())
+
+
+# ---------------------------------------------------------------- N_q != N_k (queries = the last N_q positions)
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,N,Bc", [(1, 200, 64), (40, 100, 32), (64, 192, 64), (37, 37, 16), (5, 130, 128)])
+def test_rectangular_without_p_quant_equals_standard_attention(Nq, N, Bc, causal):
+    # fp64 reference with the library softmax; causal: query i sees keys j <= i + (N - Nq)
+    rng = np.random.default_rng(30)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 2, N, 32, score_sigma=2.0)
+    Qq, sQ = Qq[:, :Nq], sQ[:, :Nq]                      # any Nq rows will do as queries
+    got = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc, p_quant=False)["O"].reshape(2, Nq, 32)
+    S = np.einsum("hik,hjk->hij", dequant(Qq, sQ), dequant(Kq, sK))
+    if causal:
+        vis = np.arange(N)[None, :] <= (np.arange(Nq)[:, None] + (N - Nq))
+        S = np.where(vis[None], S, -np.inf)
+    ref = np.einsum("hij,hjc->hic", scipy.special.softmax(S, axis=-1),
+                    Vq.astype(np.float64) * sV[:, None, None].astype(np.float64))
+    assert np.allclose(got, ref, rtol=2e-5, atol=2e-6 * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("Bc", [32, 128])
+def test_rectangular_rows_are_rows_of_the_square_problem(Bc):
+    # Rows are independent (Algorithm 1 treats each Q_i block alone): the last Nq rows of the square causal
+    # problem ARE the causal rectangular problem, bit for bit; without a mask any subset of rows is.
+    rng = np.random.default_rng(31)
+    N, Nq, d = 160, 48, 32
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 2, N, d, score_sigma=2.0)
+    for causal in (False, True):
+        full = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc, want_P=True)
+        rect = oracle.int_flash_attn_fwd(Qq[:, N - Nq:], Kq, Vq, sQ[:, N - Nq:], sK, sV, causal, Bc, want_P=True)
+        pick = (np.arange(2)[:, None] * N + np.arange(N - Nq, N)[None, :]).ravel()
+        for key in ("O", "l", "m", "P"):
+            assert np.array_equal(rect[key], full[key][pick]), key
+    # a single query (decode): the mask changes nothing, and it sees every key
+    one = oracle.int_flash_attn_fwd(Qq[:, -1:], Kq, Vq, sQ[:, -1:], sK, sV, True, Bc, want_P=True)
+    assert np.array_equal(one["O"], oracle.int_flash_attn_fwd(Qq[:, -1:], Kq, Vq, sQ[:, -1:], sK, sV, False, Bc)["O"])
+    assert (one["P"] > 0).sum() > 0 and one["P"].shape == (2, N)
+    # first of the Nq causal rows sees exactly N - Nq + 1 keys
+    P0 = oracle.int_flash_attn_fwd(Qq[:, N - Nq:], Kq, Vq, sQ[:, N - Nq:], sK, sV, True, Bc, want_P=True)["P"][0]
+    assert not P0[N - Nq + 1:].any()
