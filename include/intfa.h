@@ -112,6 +112,18 @@ int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, cons
                           void *hip_stream);
 
 /*
+ * Algorithm 1 for N_q query rows against N_k keys (the paper states it for N_q = N_k; rows are independent, so
+ * only the loop bounds change): a chunk of queries against a longer key sequence, or one query (decoding).
+ *   Q_i8 [B, H, Nq, d], s_Q [B, H, Nq];  K_i8, V_i8 [B, H, Nk, d], s_K [B, H, Nk];  s_V [B, H];  O [B, H, Nq, d]
+ *   causal = 1: the queries are the LAST Nq positions of the key sequence, i.e. query i sees keys
+ *   j <= i + (Nk - Nq); needs Nk >= Nq (else IFA_ERR_UNSUPPORTED: some query would see no key).
+ * Everything else as int_flash_attn_fwd_ex, which is this call with Nq = Nk.
+ */
+int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                            const float *s_Q, const float *s_K, const float *s_V,
+                            int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream);
+
+/*
  * Per-block quantization of V -- the scheme the paper names as its next step (Section 3.2, footnote;
  * Section 5: "we will use per-block quantization to optimize the implementation of the V matrix").
  * One scale per (head, block of block_keys consecutive keys) = per V_j of Algorithm 1:

@@ -20,6 +20,7 @@ SIGNATURES = {
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
+    "int_flash_attn_fwd_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
     "quantize_blockwise": (_i, [_vp, _i, _l, _l, _i, _i, _vp, _vp, _vp]),
     "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "ifa_block_cols": (_i, [_i, _i]),
@@ -127,21 +128,29 @@ def quantize_blockwise(X, block_keys):
 
 
 def int_flash_attn_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None):
-    """Algorithm 1 on [B, H, N, d] int8 tensors.  Returns O [B, H, N, d] (fp16 unless out_dtype/out says otherwise).
+    """Algorithm 1 on int8 tensors Q [B, H, Nq, d], K, V [B, H, Nk, d] (Nq = Nk in the paper; under the causal mask
+    the queries are the last Nq positions).  Returns O [B, H, Nq, d] (fp16 unless out_dtype/out says otherwise).
     s_V [B, H] is the tensor-level scale of V; a 3-d s_V [B, H, ceil(N/B_c)] selects the per-block V scales."""
     import torch
     B, H, N, d = Q_i8.shape
+    Nk = K_i8.shape[2]
     if out is None:
         out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
+    args = (_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
+            _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32))
+    tail = (d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
     if s_V.dim() == 3:
+        if Nk != N:
+            raise IntfaError("per-block s_V is built for Nq == Nk only")
         if s_V.shape != (B, H, -(-N // block_cols(d, causal))):
             raise IntfaError(f"per-block s_V has shape {tuple(s_V.shape)}")
-        fn = lib().int_flash_attn_fwd_vblock
+        code = lib().int_flash_attn_fwd_vblock(*args, B, H, N, *tail)
+    elif Nk != N:
+        if K_i8.shape != (B, H, Nk, d) or V_i8.shape != K_i8.shape or s_K.shape != (B, H, Nk) or s_Q.shape != (B, H, N):
+            raise IntfaError("Q/K/V/scale shapes do not agree")
+        code = lib().int_flash_attn_fwd_rect(*args, B, H, N, Nk, *tail)
     else:
-        fn = lib().int_flash_attn_fwd_ex
-    code = fn(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
-                                       _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32),
-                                       B, H, N, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
+        code = lib().int_flash_attn_fwd_ex(*args, B, H, N, *tail)
     _check(code, "int_flash_attn_fwd")
     return out
 

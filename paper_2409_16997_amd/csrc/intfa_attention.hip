@@ -323,34 +323,39 @@ template <int D, bool CAUSAL, bool VB, typename OutT>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
-    int heads, int N, int head_group, OutT *__restrict__ O) {
+    int heads, int Nq, int Nk, int head_group, OutT *__restrict__ O) {
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
 
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-    const int T_r = (N + BR - 1) / BR;                           // the last query / key block may be ragged
+    const int T_r = (Nq + BR - 1) / BR;                          // the last query / key block may be ragged
+    const int T_c = (Nk + BC - 1) / BC;
+    // Under the mask the queries are the LAST Nq positions of the key sequence: query i sees keys <= i + shift.
+    const int shift = CAUSAL ? Nk - Nq : 0;
 
     int head, qord;
     map_workgroup(blockIdx.x, heads, T_r, head_group, head, qord);
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;                           // this lane's query inside the block
     const int q_head = qb * BR + q_local;                        // this lane's query inside the head
-    const bool q_valid = q_head < N;                             // rows past N are computed on a clamped copy, never stored
-    const long qrow = static_cast<long>(head) * N + min(q_head, N - 1);
+    const bool q_valid = q_head < Nq;                            // rows past Nq are computed on a clamped copy, never stored
+    const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);
 
-    const int8_t *Kh = K + static_cast<long>(head) * N * D;
-    const int8_t *Vh = V + static_cast<long>(head) * N * D;
-    const float *sKh = sK + static_cast<long>(head) * N;
+    const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
+    const int8_t *Vh = V + static_cast<long>(head) * Nk * D;
+    const float *sKh = sK + static_cast<long>(head) * Nk;
     const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
     const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
     const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
-    const int nblocks = CAUSAL ? (qb + 1) : T_r;                 // B_r == B_c, so T_c == T_r
+    // key blocks this workgroup walks: up to the last key any of its queries sees
+    const int first_q = qb * BR;
+    const int nblocks = CAUSAL ? min(Nk - 1, first_q + BR - 1 + shift) / BC + 1 : T_c;
 
-    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
-    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(N) * D);
-    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(N) * 4);
+    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(Nk) * 4);
 
     // line 5: Q_i and s_Q,i.  B operand: lane (r, g) holds bytes d = 32*kk + 16*g .. +15 of query r.
     v4i qf[D / 32];
@@ -378,11 +383,12 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     wait_all_memory();
     __syncthreads();
 
-    const bool ragged = (N % BC) != 0;                           // only the last key block can hold keys >= N
-    const bool masked_last = CAUSAL || ragged;
-    const int nfull = masked_last ? nblocks - 1 : nblocks;       // blocks in which every key counts
-    // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_r]
-    const float *sVh = VB ? sV + static_cast<long>(head) * T_r : sV + head;
+    // Blocks in which every key counts for every query of the workgroup come first: all keys below Nk and, under
+    // the mask, at or before the first query's last visible key.  The rest -- the block(s) the causal diagonal
+    // crosses, the ragged last block -- run the masked code.
+    const int nfull = min(nblocks, CAUSAL ? min(Nk / BC, (first_q + shift + 1) / BC) : Nk / BC);
+    // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_c]
+    const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
     float sv_prev = 1.0f;
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
@@ -396,18 +402,39 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
-    if (masked_last) {   // the block on the causal diagonal, or the ragged last block, comes last
-        const int cur = nfull & 1;
-        const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
-        // kept keys of this block: index <= query (mask) -- which, for a query < N, also excludes keys >= N -- or
-        // index < N - first key of the block (no mask, ragged N)
-        const int tail = N - 1 - nfull * BC;
-        const int klimit = CAUSAL ? q_local : tail;
-        const int last_tile = CAUSAL ? wave : (tail >> 5);
-        const float sv_j = VB ? sVh[nfull] : 1.0f;
-        const float oscale = VB ? sv_prev / sv_j : 1.0f;
-        sv_prev = sv_j;
-        process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, last_tile, g, oscale, none, st);
+    // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
+    // ragged last block is one of them or, without a mask, the only one).  They are written out one after the
+    // other rather than as a loop so that the staging offsets are dead once the second one has been requested.
+    auto masked_block = [&](int jb) {
+        const int cur = jb & 1, j0 = jb * BC;
+        // kept keys of this block: index inside the block <= klimit (may be negative: none).  Tiles after tile
+        // wlim / 32 hold no kept key for any lane of this wavefront.
+        const int tail = Nk - 1 - j0;
+        const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;
+        const int wlim = CAUSAL ? min(first_q + 32 * wave + 31 + shift - j0, tail) : tail;
+        if (wlim >= 0) {                                         // wave-uniform: this wavefront sees part of the block
+            const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
+            const float sv_j = VB ? sVh[jb] : 1.0f;
+            const float oscale = VB ? sv_prev / sv_j : 1.0f;
+            sv_prev = sv_j;
+            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), g, oscale, none, st);
+        }
+    };
+    if (nfull < nblocks) {
+        const bool second = nfull + 1 < nblocks;
+        if (second) {                                            // line 8 for the second masked block
+            const int nxt = (nfull & 1) ^ 1, j1 = (nfull + 1) * BC;
+            const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D, skbuf + nxt * BC * 4, true};
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(pf, lo, wave, i); prefetch_v_piece<D>(pf, lo, wave, i); }
+            prefetch_sk(pf, wave, lane);
+        }
+        masked_block(nfull);
+        if (second) {
+            wait_all_memory();
+            __syncthreads();
+            masked_block(nfull + 1);
+        }
     }
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
@@ -494,32 +521,34 @@ hipStream_t g_stream = nullptr;
 
 template <int D, bool CAUSAL, bool VB, typename OutT>
 int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
-               int heads, int N, void *O, hipStream_t st) {
-    const long wgs = static_cast<long>(heads) * ((N + BR - 1) / BR);
+               int heads, int Nq, int Nk, void *O, hipStream_t st) {
+    const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, VB, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, sV, heads, N, HEAD_GROUP, static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, sV, heads, Nq, Nk, HEAD_GROUP, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
 template <int D, bool CAUSAL, bool VB>
 int launch_fwd_dtype(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK,
-                     const float *sV, int heads, int N, void *O, int o_dtype, hipStream_t st) {
+                     const float *sV, int heads, int Nq, int Nk, void *O, int o_dtype, hipStream_t st) {
     switch (o_dtype) {
-    case IFA_F32: return launch_fwd<D, CAUSAL, VB, float>(Q, K, V, sQ, sK, sV, heads, N, O, st);
-    case IFA_F16: return launch_fwd<D, CAUSAL, VB, __half>(Q, K, V, sQ, sK, sV, heads, N, O, st);
-    default: return launch_fwd<D, CAUSAL, VB, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, N, O, st);
+    case IFA_F32: return launch_fwd<D, CAUSAL, VB, float>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+    case IFA_F16: return launch_fwd<D, CAUSAL, VB, __half>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+    default: return launch_fwd<D, CAUSAL, VB, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
     }
 }
 
 // validation and dispatch shared by the tensor-level and the block-level V scale entry points
 template <bool VB>
 int fwd_entry(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8, const float *s_Q,
-              const float *s_K, const float *s_V, int B, int H, int N, int d, int causal, void *O, int o_dtype,
+              const float *s_K, const float *s_V, int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype,
               void *hip_stream) {
     if (!Q_i8 || !K_i8 || !V_i8 || !s_Q || !s_K || !s_V || !O) return IFA_ERR_NULL;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return IFA_ERR_SHAPE;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || d <= 0) return IFA_ERR_SHAPE;
     const long heads = static_cast<long>(B) * H;
+    const int N = Nq > Nk ? Nq : Nk;
     if (heads > (1L << 40) / N / d) return IFA_ERR_SHAPE;
+    if (causal && Nk < Nq) return IFA_ERR_UNSUPPORTED;           // a query with no visible key
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
     if (static_cast<long>(N) * d > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
@@ -533,10 +562,10 @@ int fwd_entry(const signed char *Q_i8, const signed char *K_i8, const signed cha
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int hd = static_cast<int>(heads);
     if (d == 128)
-        return causal ? launch_fwd_dtype<128, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
-                      : launch_fwd_dtype<128, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
-    return causal ? launch_fwd_dtype<64, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st)
-                  : launch_fwd_dtype<64, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, N, O, o_dtype, st);
+        return causal ? launch_fwd_dtype<128, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st)
+                      : launch_fwd_dtype<128, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st);
+    return causal ? launch_fwd_dtype<64, true, VB>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st)
+                  : launch_fwd_dtype<64, false, VB>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st);
 }
 
 }  // namespace
@@ -568,13 +597,19 @@ extern "C" int ifa_block_cols(int d, int causal) {
 extern "C" int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                                      const float *s_Q, const float *s_K, const float *s_V, int B, int H, int N, int d,
                                      int causal, void *O, int o_dtype, void *hip_stream) {
-    return fwd_entry<false>(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, N, d, causal, O, o_dtype, hip_stream);
+    return fwd_entry<false>(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, N, N, d, causal, O, o_dtype, hip_stream);
 }
 
 extern "C" int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                                          const float *s_Q, const float *s_K, const float *s_Vb, int B, int H, int N,
                                          int d, int causal, void *O, int o_dtype, void *hip_stream) {
-    return fwd_entry<true>(Q_i8, K_i8, V_i8, s_Q, s_K, s_Vb, B, H, N, d, causal, O, o_dtype, hip_stream);
+    return fwd_entry<true>(Q_i8, K_i8, V_i8, s_Q, s_K, s_Vb, B, H, N, N, d, causal, O, o_dtype, hip_stream);
+}
+
+extern "C" int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                       const float *s_Q, const float *s_K, const float *s_V, int B, int H, int Nq, int Nk,
+                                       int d, int causal, void *O, int o_dtype, void *hip_stream) {
+    return fwd_entry<false>(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, Nq, Nk, d, causal, O, o_dtype, hip_stream);
 }
 
 extern "C" int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,

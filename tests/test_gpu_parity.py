@@ -238,6 +238,56 @@ def test_ragged_sequence_lengths(ifa, N, d, causal):
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,d", [(1, 1000, 128), (1, 128, 64), (128, 512, 128), (100, 333, 128), (256, 1024, 64),
+                                     (37, 37, 128), (130, 131, 128), (64, 4096, 128), (300, 200, 128), (513, 640, 64)])
+def test_rectangular_problems(ifa, Nq, Nk, d, causal):
+    # Nq query rows against Nk keys: a chunk of queries against a longer sequence, or one query.  Under the mask
+    # the queries are the last Nq positions (query i sees keys <= i + Nk - Nq), so the diagonal crosses key blocks
+    # at any offset; Nk < Nq is allowed without the mask only.
+    if causal and Nk < Nq:
+        p = lambda t: ctypes_ptr(t)
+        z8 = torch.zeros((1, 1, max(Nq, Nk), d), dtype=torch.int8, device="cuda")
+        zf = torch.ones((1, 1, max(Nq, Nk)), dtype=torch.float32, device="cuda")
+        O = torch.empty((1, 1, Nq, d), dtype=torch.float16, device="cuda")
+        rc = ifa.lib().int_flash_attn_fwd_rect(p(z8), p(z8), p(z8), p(zf), p(zf), p(zf), 1, 1, Nq, Nk, d, 1, p(O), 1, None)
+        assert rc == -4
+        return
+    H = 3
+    rng = np.random.default_rng(Nq * 7 + Nk + d)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, max(Nq, Nk), d, score_sigma=2.0)
+    Qq, sQ = np.ascontiguousarray(Qq[:, :Nq]), np.ascontiguousarray(sQ[:, :Nq])
+    Kq, Vq, sK = np.ascontiguousarray(Kq[:, :Nk]), np.ascontiguousarray(Vq[:, :Nk]), np.ascontiguousarray(sK[:, :Nk])
+    guard = 64
+    Obuf = torch.full((H * Nq + guard, d), 12345.0, dtype=torch.float32, device="cuda")
+    O = Obuf[:H * Nq].view(1, H, Nq, d)
+    ifa.int_flash_attn_fwd(dev(Qq[None]), dev(Kq[None]), dev(Vq[None]), dev(sQ[None]), dev(sK[None]), dev(sV[None]),
+                           causal=causal, out=O)
+    torch.cuda.synchronize()
+    assert bool((Obuf[H * Nq:] == 12345.0).all())
+    check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), Qq, Kq, Vq, sQ, sK, sV, causal,
+                         label=f"rect Nq={Nq} Nk={Nk} d={d} causal={causal}")
+
+
+def ctypes_ptr(t):
+    import ctypes
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def test_rectangular_rows_equal_the_square_kernel_rows(ifa):
+    # the last Nq rows of the square causal problem, computed as a rectangular call: same bits
+    H, N, Nq, d = 4, 1024, 200, 128
+    rng = np.random.default_rng(77)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, N, d, score_sigma=2.0)
+    args = lambda q, sq: (dev(q[None]), dev(Kq[None]), dev(Vq[None]), dev(sq[None]), dev(sK[None]), dev(sV[None]))
+    for causal in (False, True):
+        full = ifa.int_flash_attn_fwd(*args(Qq, sQ), causal=causal, out_dtype=torch.float32)
+        rect = ifa.int_flash_attn_fwd(*args(np.ascontiguousarray(Qq[:, N - Nq:]), np.ascontiguousarray(sQ[:, N - Nq:])),
+                                      causal=causal, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(rect, full[:, :, N - Nq:])
+
+
+@pytest.mark.parametrize("causal", [False, True])
 def test_random_int8_grid_inputs_wide_scores(ifa, causal):
     # int8 values over the whole range with score spreads from flat to nearly one-hot rows
     rng = np.random.default_rng(5)
