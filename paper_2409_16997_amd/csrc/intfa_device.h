@@ -92,12 +92,15 @@ template <> struct Store4<float> {
     }
 };
 template <> struct Store4<__half> {
-    static __device__ __forceinline__ void put(__half *p, float a, float b, float c, float d) {
+    static __device__ __forceinline__ uint2 pack(float a, float b, float c, float d) {
         __half2 lo = __floats2half2_rn(a, b), hi = __floats2half2_rn(c, d);
         uint2 w;
         w.x = *reinterpret_cast<uint32_t *>(&lo);
         w.y = *reinterpret_cast<uint32_t *>(&hi);
-        *reinterpret_cast<uint2 *>(p) = w;
+        return w;
+    }
+    static __device__ __forceinline__ void put(__half *p, float a, float b, float c, float d) {
+        *reinterpret_cast<uint2 *>(p) = pack(a, b, c, d);
     }
 };
 template <> struct Store4<__hip_bfloat16> {
@@ -105,13 +108,49 @@ template <> struct Store4<__hip_bfloat16> {
         uint32_t u = __float_as_uint(x);
         return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     }
-    static __device__ __forceinline__ void put(__hip_bfloat16 *p, float a, float b, float c, float d) {
+    static __device__ __forceinline__ uint2 pack(float a, float b, float c, float d) {
         uint2 w;
         w.x = rne(a) | (rne(b) << 16);
         w.y = rne(c) | (rne(d) << 16);
-        *reinterpret_cast<uint2 *>(p) = w;
+        return w;
+    }
+    static __device__ __forceinline__ void put(__hip_bfloat16 *p, float a, float b, float c, float d) {
+        *reinterpret_cast<uint2 *>(p) = pack(a, b, c, d);
     }
 };
+
+#if defined(__HIP_DEVICE_COMPILE__)
+// Writes a wavefront's 32 x D output tile (2-byte elements) through a private LDS region of 64 D bytes so that the
+// global stores are whole rows: in the accumulator layout a lane holds 4 consecutive d of one row per register
+// group, and storing those directly costs one 8-byte piece per row and instruction.  Staged, lane t stores 16
+// contiguous bytes and 16 (D = 128) or 8 (D = 64) lanes cover a row.  The 16-byte chunks of a row are XOR-swizzled
+// by the row so that the column-wise writes spread over the banks.  Only this wavefront touches `stage`; LDS
+// operations of one wavefront complete in order, so no barrier is needed between the two halves.
+//   val(dt, v): element d = 32*dt + 8*(v/4) + 4*g + v%4 of row r = lane % 32 (g = lane / 32), already scaled
+//   rows_valid: rows at or beyond it are not stored;  orow0: address of row 0 of the tile, row stride D elements
+template <int D, typename OutT, typename F>
+__device__ __forceinline__ void store_tile_staged(lds_ptr stage, OutT *orow0, int rows_valid, int lane, F val) {
+    static_assert(sizeof(OutT) == 2, "staged store is for 2-byte outputs");
+    constexpr int CH = D * 2 / 16;                 // 16-byte chunks per row
+    const int r = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            const uint2 w = Store4<OutT>::pack(val(dt, 4 * vq), val(dt, 4 * vq + 1), val(dt, 4 * vq + 2), val(dt, 4 * vq + 3));
+            *reinterpret_cast<LDS_AS uint2 *>(stage + r * (2 * D) + (((4 * dt + vq) ^ (r & (CH - 1))) * 16) + 8 * g) = w;
+        }
+    constexpr int ROWS_PER_PASS = 64 / CH;
+    const int c = lane % CH, rr = lane / CH;
+#pragma unroll
+    for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
+        const int row = pass * ROWS_PER_PASS + rr;
+        const v4i x = *reinterpret_cast<LDS_AS const v4i *>(stage + row * (2 * D) + ((c ^ (row & (CH - 1))) * 16));
+        if (row < rows_valid) *reinterpret_cast<v4i *>(orow0 + static_cast<long>(row) * D + 8 * c) = x;
+    }
+}
+#endif
+
 
 }  // namespace ifa_dev
 
