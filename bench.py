@@ -220,6 +220,16 @@ def main():
             "fp8_e4m3_tensor_scale": baselines.mre(baselines.attention_fp8_tensor(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
         }
 
+        # ---- the paper's literal convention (S = Q K^T, no 1/sqrt(d)): same codes, s_Q without the fold
+        if not half:
+            s = state
+            O_lit = ifa.int_flash_attn_fwd(s["Qq"][:1, :1], s["Kq"][:1, :1], s["Vq"][:1, :1],
+                                           (s["sQ"][:1, :1] * math.sqrt(w.d)).contiguous(), s["sK"][:1, :1],
+                                           s["sV"][:1, :1], causal=w.causal, out_dtype=torch.float32)
+            ref_lit = oracle.attention_fp64(q[None], k[None], v[None], causal=w.causal, scale=1.0, row_idx=rows)
+            result["mre_vs_fp64"]["int8_full, literal S = Q K^T (no 1/sqrt(d))"] = \
+                baselines.mre(O_lit[0, 0].cpu().numpy()[rows], ref_lit)["sum_ratio"]
+
     print(json.dumps(result))
 
 
