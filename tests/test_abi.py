@@ -95,3 +95,11 @@ def test_argument_validation_happens_on_the_host(L):
     assert hf(p, p, p, p, p, 1, 1, 1 << 29, 128, 0, p, 1, None) == -4   # one head of fp16 V must stay below 2 GiB
     assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
     assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the build is single-GPU by design: bench.py says so instead of running
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr

@@ -87,6 +87,15 @@ def test_ragged_sequence_lengths(ifa, N, d, causal):
     check(ifa, O.cpu().numpy().reshape(-1, d), x, causal, d, label=f"ragged N={N} d={d} causal={causal}")
 
 
+@pytest.mark.parametrize("B,H", [(5, 8), (3, 8), (1, 7)])
+def test_head_counts_and_grid_shapes(ifa, B, H):
+    N, d = 256, 128
+    w = workloads.custom("t", B, H, N, d, True, dist="normal", seed=13 * B + H)
+    x = inputs(w)
+    O = run(ifa, x, B, H, N, d, True).cpu().numpy()
+    check(ifa, O.reshape(-1, d), x, True, d, label=f"heads {B}x{H}")
+
+
 def test_unscaled_scores_and_wide_range(ifa):
     # the paper's literal S = Q K^T (no 1/sqrt(d)): scores of standard deviation ~11, most weights underflow fp16
     w = workloads.custom("t", 1, 4, 512, 128, False, dist="normal", seed=99)

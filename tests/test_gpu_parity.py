@@ -217,6 +217,18 @@ def test_shapes_masks_distributions(ifa, B, H, N, d, causal, dist):
                          label=f"{B}x{H}x{N}x{d} causal={causal} {dist}")
 
 
+@pytest.mark.parametrize("B,H", [(5, 8), (3, 8), (9, 8), (1, 7), (3, 3), (1, 16)])
+def test_head_counts_and_grid_shapes(ifa, B, H):
+    # head counts that fill the XCD groups exactly, leave a short last group (padding workgroups), or are not a
+    # multiple of 8 at all (plain grid); every head must come out, each exactly once
+    N, d = 256, 64
+    w = workloads.custom("t", B, H, N, d, True, dist="normal", seed=31 * B + H)
+    x = quantized_inputs(w, scaled=True)
+    O = run_gpu(ifa, x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], B, H, True).cpu().numpy()
+    check_against_oracle(ifa, O.reshape(-1, d), x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], True,
+                         label=f"heads {B}x{H}")
+
+
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("N,d", [(1, 128), (37, 64), (127, 128), (129, 128), (200, 64), (333, 128), (1000, 128), (515, 64)])
 def test_ragged_sequence_lengths(ifa, N, d, causal):
