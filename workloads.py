@@ -30,7 +30,7 @@ class Workload:
     N: int
     d: int
     causal: bool
-    dist: str          # "normal" | "uniform_outlier" | "student_t3"
+    dist: str          # "normal" | "uniform" | "uniform_outlier" | "student_t3"
     in_dtype: str      # numpy dtype name of the real-valued Q, K, V
     out_dtype: str     # dtype the attention output is stored in
     seed: int
@@ -61,6 +61,8 @@ def head_tensor(w: Workload, tensor: str, head: int) -> np.ndarray:
     rng = np.random.default_rng([w.seed, TENSOR_IDS[tensor], head])
     if w.dist == "normal":
         x = rng.standard_normal((w.N, w.d), dtype=np.float32)
+    elif w.dist == "uniform":                      # U(-0.5, 0.5), the second distribution of Section 4.2
+        x = rng.random((w.N, w.d), dtype=np.float32) - np.float32(0.5)
     elif w.dist == "uniform_outlier":
         x = rng.random((w.N, w.d), dtype=np.float32) - np.float32(0.5)
         ch = rng.choice(w.d, size=4, replace=False)
