@@ -159,6 +159,12 @@ int int_flash_attn_fwd_half(const signed char *Q_i8, const signed char *K_i8, co
                             const float *s_Q, const float *s_K,
                             int B, int H, int N, int d, int causal, void *O, int o_dtype, void *hip_stream);
 
+/* The half-INT8 variant for N_q query rows against N_k keys; shapes and the causal convention as in
+ * int_flash_attn_fwd_rect (V_f16 is [B, H, Nk, d]).  int_flash_attn_fwd_half is this call with Nq = Nk. */
+int int_flash_attn_fwd_half_rect(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
+                                 const float *s_Q, const float *s_K,
+                                 int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream);
+
 /* Key-block size of the half-INT8 kernel for (d, causal); 0 if that pair is unsupported. */
 int ifa_block_cols_half(int d, int causal);
 

@@ -46,7 +46,7 @@ def _load():
         lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
         lib.orc_round_to_half.argtypes = [ctypes.c_float]
         lib.orc_round_to_half.restype = ctypes.c_float
-        lib.orc_int_flash_attn_fwd_half.argtypes = [vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, vp, i64, vp, vp, vp]
+        lib.orc_int_flash_attn_fwd_half.argtypes = [vp, vp, vp, vp, vp, i32, i32, i64, i64, i32, i32, i32, vp, i64, vp, vp, vp]
         lib.orc_int_flash_attn_fwd_half.restype = None
         for f in (lib.orc_quantize_rows, lib.orc_qk_i32, lib.orc_pv_i32,
                   lib.orc_int_flash_attn_fwd, lib.orc_attention_fp64):
@@ -194,24 +194,26 @@ def round_to_half(x):
 
 def int_flash_attn_fwd_half(Q, K, V, sQ, sK, causal, Bc, row_idx=None):
     """Half-INT8 variant (Section 4): INT8 Q, K with token-level scales, fp16 V, P~ = fp16(exp(S - m)).
-    Q, K int8 [heads, N, d]; V fp16 [heads, N, d]; sQ, sK fp32 [heads, N].  Returns a dict O, l, m."""
+    Q int8 [heads, Nq, d], sQ fp32 [heads, Nq]; K int8, V fp16 [heads, N, d], sK fp32 [heads, N].  Returns a dict O, l, m."""
     Q, K = _c(Q, np.int8), _c(K, np.int8)
     assert V.dtype == np.float16
     Vf = _c(V, np.float32)                      # exact widening
-    heads, N, d = Q.shape
+    heads, Nq, d = Q.shape
+    N = K.shape[1]
     sQ, sK = _c(sQ, np.float32), _c(sK, np.float32)
-    assert K.shape == Q.shape and Vf.shape == Q.shape and sQ.shape == (heads, N) and sK.shape == (heads, N)
+    assert K.shape == (heads, N, d) and Vf.shape == K.shape and sQ.shape == (heads, Nq) and sK.shape == (heads, N)
+    assert not causal or N >= Nq
     if row_idx is not None:
         row_idx = _c(row_idx, np.int64)
         n = row_idx.size
-        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * N)
+        assert n == 0 or (row_idx.min() >= 0 and row_idx.max() < heads * Nq)
     else:
-        n = heads * N
+        n = heads * Nq
     O = np.empty((n, d), np.float32)
     l = np.empty(n, np.float32)
     m = np.empty(n, np.float32)
     if n:
-        _load().orc_int_flash_attn_fwd_half(_p(Q), _p(K), _p(Vf), _p(sQ), _p(sK), 1, heads, N, d,
+        _load().orc_int_flash_attn_fwd_half(_p(Q), _p(K), _p(Vf), _p(sQ), _p(sK), 1, heads, Nq, N, d,
                                             int(bool(causal)), int(Bc), _p(row_idx), n, _p(O), _p(l), _p(m))
     return {"O": O, "l": l, "m": m}
 

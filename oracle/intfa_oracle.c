@@ -278,15 +278,17 @@ float orc_round_to_half(float x)
  *   l  = alpha l + rowsum(P~)        the ROUNDED weights, summed in fp32 (as line 12 sums the rounded P)
  *   O  = alpha O + P~ V_j            fp16 x fp16 products are exact in fp32; fp32 accumulation in key order
  *   O  = O / l                       no s_V: V is not quantized
- * Vf holds the caller's fp16 V widened to fp32 [B*H, N, d].  Other arguments as orc_int_flash_attn_fwd.
+ * Vf holds the caller's fp16 V widened to fp32 [B*H, N, d]; Q is [B*H, Nq, d].  Other arguments as
+ * orc_int_flash_attn_fwd.
  */
 void orc_int_flash_attn_fwd_half(const int8_t *Q, const int8_t *K, const float *Vf,
                                  const float *sQ, const float *sK,
-                                 int B, int H, int64_t N, int d, int causal, int Bc,
+                                 int B, int H, int64_t Nq, int64_t N, int d, int causal, int Bc,
                                  const int64_t *row_idx, int64_t n_rows,
                                  float *O, float *l_out, float *m_out)
 {
-    const int64_t total = (int64_t)B * H * N;
+    const int64_t total = (int64_t)B * H * Nq;
+    const int64_t shift = N - Nq;   /* causal: query i sees keys j <= i + shift, as in orc_int_flash_attn_fwd */
     if (row_idx == NULL) n_rows = total;
 
 #pragma omp parallel
@@ -298,7 +300,7 @@ void orc_int_flash_attn_fwd_half(const int8_t *Q, const int8_t *K, const float *
 #pragma omp for schedule(dynamic, 16)
         for (int64_t r = 0; r < n_rows; ++r) {
             const int64_t g = row_idx ? row_idx[r] : r;
-            const int64_t head = g / N, i = g % N;
+            const int64_t head = g / Nq, i = g % Nq + (causal ? shift : 0);   /* i: last visible key if causal */
             const int8_t *q = Q + g * d;
             const int8_t *Kh = K + head * N * d;
             const float *Vh = Vf + head * N * d;

@@ -25,6 +25,7 @@ SIGNATURES = {
     "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "ifa_block_cols": (_i, [_i, _i]),
     "int_flash_attn_fwd_half": (_i, [_vp] * 5 + [_i] * 5 + [_vp, _i, _vp]),
+    "int_flash_attn_fwd_half_rect": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _i, _vp]),
     "ifa_block_cols_half": (_i, [_i, _i]),
     "ifa_debug_qk_i32": (_i, [_vp, _vp, _i, _i, _vp]),
     "ifa_debug_pv_i32": (_i, [_vp, _vp, _i, _i, _vp]),
@@ -160,14 +161,18 @@ def block_cols(d: int, causal: bool) -> int:
 
 
 def int_flash_attn_fwd_half(Q_i8, K_i8, V_f16, s_Q, s_K, causal=False, out_dtype=None, out=None):
-    """Half-INT8 variant: int8 Q, K with token-level scales, fp16 V as is.  Returns O [B, H, N, d]."""
+    """Half-INT8 variant: int8 Q [B, H, Nq, d], K [B, H, Nk, d] with token-level scales, fp16 V [B, H, Nk, d] as is
+    (Nq = Nk in the paper; under the mask the queries are the last Nq positions).  Returns O [B, H, Nq, d]."""
     import torch
     B, H, N, d = Q_i8.shape
     if out is None:
         out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
-    code = lib().int_flash_attn_fwd_half(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_f16, torch.float16),
-                                         _dev(s_Q, torch.float32), _dev(s_K, torch.float32),
-                                         B, H, N, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
+    Nk = K_i8.shape[2]
+    if K_i8.shape != (B, H, Nk, d) or V_f16.shape != K_i8.shape or s_K.shape != (B, H, Nk) or s_Q.shape != (B, H, N):
+        raise IntfaError("Q/K/V/scale shapes do not agree")
+    code = lib().int_flash_attn_fwd_half_rect(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_f16, torch.float16),
+                                              _dev(s_Q, torch.float32), _dev(s_K, torch.float32),
+                                              B, H, N, Nk, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
     _check(code, "int_flash_attn_fwd_half")
     return out
 

@@ -235,36 +235,39 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
 template <int D, bool CAUSAL, typename OutT>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const _Float16 *__restrict__ V,
-    const float *__restrict__ sQ, const float *__restrict__ sK, int heads, int N, int head_group, OutT *__restrict__ O) {
+    const float *__restrict__ sQ, const float *__restrict__ sK, int heads, int Nq, int Nk, int head_group, OutT *__restrict__ O) {
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ SmemH<D> sm;
     constexpr int DT = D / 32;
 
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int T_r = (N + BR - 1) / BR;
-    const int T_c = (N + BCH - 1) / BCH;
+    const int T_r = (Nq + BR - 1) / BR;
+    const int T_c = (Nk + BCH - 1) / BCH;
+    // Under the mask the queries are the LAST Nq positions of the key sequence: query i sees keys <= i + shift.
+    const int shift = CAUSAL ? Nk - Nq : 0;
 
     int head, qord;
     map_workgroup(blockIdx.x, heads, T_r, head_group, head, qord);
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;
     const int q_head = qb * BR + q_local;
-    const bool q_valid = q_head < N;                             // rows past N are computed on a clamped copy, never stored
-    const long qrow = static_cast<long>(head) * N + min(q_head, N - 1);
+    const bool q_valid = q_head < Nq;                            // rows past Nq are computed on a clamped copy, never stored
+    const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);
 
-    const int8_t *Kh = K + static_cast<long>(head) * N * D;
-    const _Float16 *Vh = V + static_cast<long>(head) * N * D;
-    const float *sKh = sK + static_cast<long>(head) * N;
+    const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
+    const _Float16 *Vh = V + static_cast<long>(head) * Nk * D;
+    const float *sKh = sK + static_cast<long>(head) * Nk;
     const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
     const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
     const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
-    // key blocks this workgroup walks: all of them, or those that hold a key <= its last query
-    const int nblocks = CAUSAL ? min(T_c, (qb + 1) * (BR / BCH)) : T_c;
+    // key blocks this workgroup walks: up to the last key any of its queries sees
+    const int first_q = qb * BR;
+    const int nblocks = CAUSAL ? min(Nk - 1, first_q + BR - 1 + shift) / BCH + 1 : T_c;
 
-    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(N) * D);
-    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(N) * D * 2);
-    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(N) * 4);
+    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(Nk) * D * 2);
+    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(Nk) * 4);
 
     v4i qf[D / 32];
 #pragma unroll
@@ -289,11 +292,8 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     __syncthreads();
 
     // Blocks in which every key counts for every query of the workgroup come first; the rest (the two blocks that
-    // meet the causal diagonal, or the ragged last block) run the masked code.
-    const int first_q = qb * BR;
-    int nfull = nblocks;
-    if (CAUSAL) nfull = min(nfull, first_q / BCH);               // blocks entirely at or before the first query
-    if (N % BCH != 0) nfull = min(nfull, T_c - 1);
+    // meet the causal diagonal band of the workgroup's 128 queries, or the ragged last block) run the masked code.
+    const int nfull = min(nblocks, CAUSAL ? min(Nk / BCH, (first_q + shift + 1) / BCH) : Nk / BCH);
     const int wave_last_q = first_q + 32 * wave + 31;            // last query of this wavefront
     auto next_block = [&](int jb) {                              // what block jb + 1 needs staged, into the other buffers
         const int nxt = (jb & 1) ^ 1, j1 = (jb + 1) * BCH;
@@ -312,9 +312,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
         const int cur = jb & 1;
         prefetch_block<D>(next_block(jb), lo, wave, lane);
         const int j0 = jb * BCH;
-        const int tail = N - 1 - j0;                                               // last valid key of the block
-        const int klimit = CAUSAL ? min(q_head - j0, tail) : tail;                 // < 0: nothing kept
-        const int wlim = CAUSAL ? min(wave_last_q - j0, tail) : tail;
+        const int tail = Nk - 1 - j0;                                              // last valid key of the block
+        const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;         // < 0: nothing kept
+        const int wlim = CAUSAL ? min(wave_last_q + shift - j0, tail) : tail;
         const int last_tile = wlim < 0 ? -1 : min(NT - 1, wlim >> 5);
         if (last_tile >= 0)                                                        // wave-uniform
             process_block_half<D, true>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
@@ -338,21 +338,21 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
 }
 
 template <int D, bool CAUSAL, typename OutT>
-int launch_half(const int8_t *Q, const int8_t *K, const _Float16 *V, const float *sQ, const float *sK, int heads, int N,
+int launch_half(const int8_t *Q, const int8_t *K, const _Float16 *V, const float *sQ, const float *sK, int heads, int Nq, int Nk,
                 void *O, hipStream_t st) {
-    const long wgs = static_cast<long>(heads) * ((N + BR - 1) / BR);
+    const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_half_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, heads, N, HEAD_GROUP, static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, heads, Nq, Nk, HEAD_GROUP, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
 template <int D, bool CAUSAL>
 int launch_half_dtype(const int8_t *Q, const int8_t *K, const _Float16 *V, const float *sQ, const float *sK, int heads,
-                      int N, void *O, int o_dtype, hipStream_t st) {
+                      int Nq, int Nk, void *O, int o_dtype, hipStream_t st) {
     switch (o_dtype) {
-    case IFA_F32: return launch_half<D, CAUSAL, float>(Q, K, V, sQ, sK, heads, N, O, st);
-    case IFA_F16: return launch_half<D, CAUSAL, __half>(Q, K, V, sQ, sK, heads, N, O, st);
-    default: return launch_half<D, CAUSAL, __hip_bfloat16>(Q, K, V, sQ, sK, heads, N, O, st);
+    case IFA_F32: return launch_half<D, CAUSAL, float>(Q, K, V, sQ, sK, heads, Nq, Nk, O, st);
+    case IFA_F16: return launch_half<D, CAUSAL, __half>(Q, K, V, sQ, sK, heads, Nq, Nk, O, st);
+    default: return launch_half<D, CAUSAL, __hip_bfloat16>(Q, K, V, sQ, sK, heads, Nq, Nk, O, st);
     }
 }
 
@@ -363,15 +363,17 @@ extern "C" int ifa_block_cols_half(int d, int causal) {
     return (d == 64 || d == 128) ? BCH : 0;
 }
 
-extern "C" int int_flash_attn_fwd_half(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
-                                       const float *s_Q, const float *s_K, int B, int H, int N, int d, int causal,
-                                       void *O, int o_dtype, void *hip_stream) {
+namespace {
+int half_entry(const signed char *Q_i8, const signed char *K_i8, const void *V_f16, const float *s_Q, const float *s_K,
+               int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream) {
     if (!Q_i8 || !K_i8 || !V_f16 || !s_Q || !s_K || !O) return IFA_ERR_NULL;
-    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return IFA_ERR_SHAPE;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || d <= 0) return IFA_ERR_SHAPE;
     const long heads = static_cast<long>(B) * H;
+    const int N = Nq > Nk ? Nq : Nk;
     if (heads > (1L << 40) / N / d) return IFA_ERR_SHAPE;
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
+    if (causal && Nk < Nq) return IFA_ERR_UNSUPPORTED;           // a query with no visible key
     if (static_cast<long>(N) * d * 2 > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_f16) || !ifa_aligned16(O) ||
         (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3))
@@ -382,8 +384,21 @@ extern "C" int int_flash_attn_fwd_half(const signed char *Q_i8, const signed cha
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int hd = static_cast<int>(heads);
     if (d == 128)
-        return causal ? launch_half_dtype<128, true>(Q, K, V, s_Q, s_K, hd, N, O, o_dtype, st)
-                      : launch_half_dtype<128, false>(Q, K, V, s_Q, s_K, hd, N, O, o_dtype, st);
-    return causal ? launch_half_dtype<64, true>(Q, K, V, s_Q, s_K, hd, N, O, o_dtype, st)
-                  : launch_half_dtype<64, false>(Q, K, V, s_Q, s_K, hd, N, O, o_dtype, st);
+        return causal ? launch_half_dtype<128, true>(Q, K, V, s_Q, s_K, hd, Nq, Nk, O, o_dtype, st)
+                      : launch_half_dtype<128, false>(Q, K, V, s_Q, s_K, hd, Nq, Nk, O, o_dtype, st);
+    return causal ? launch_half_dtype<64, true>(Q, K, V, s_Q, s_K, hd, Nq, Nk, O, o_dtype, st)
+                  : launch_half_dtype<64, false>(Q, K, V, s_Q, s_K, hd, Nq, Nk, O, o_dtype, st);
+}
+}  // namespace
+
+extern "C" int int_flash_attn_fwd_half(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
+                                       const float *s_Q, const float *s_K, int B, int H, int N, int d, int causal,
+                                       void *O, int o_dtype, void *hip_stream) {
+    return half_entry(Q_i8, K_i8, V_f16, s_Q, s_K, B, H, N, N, d, causal, O, o_dtype, hip_stream);
+}
+
+extern "C" int int_flash_attn_fwd_half_rect(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
+                                            const float *s_Q, const float *s_K, int B, int H, int Nq, int Nk, int d,
+                                            int causal, void *O, int o_dtype, void *hip_stream) {
+    return half_entry(Q_i8, K_i8, V_f16, s_Q, s_K, B, H, Nq, Nk, d, causal, O, o_dtype, hip_stream);
 }

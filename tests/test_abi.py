@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_half", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -93,6 +93,7 @@ def test_argument_validation_happens_on_the_host(L):
     assert hf(p, p, null, p, p, 1, 1, 128, 128, 0, p, 1, None) == -1 and hf(p, p, p, p, p, 1, 0, 128, 128, 0, p, 1, None) == -2
     assert hf(p, p, p, p, p, 1, 1, 128, 128, 0, p, -1, None) == -3 and hf(p, p, p, p, p, 1, 1, 128, 256, 0, p, 1, None) == -4
     assert hf(p, p, p, p, p, 1, 1, 1 << 29, 128, 0, p, 1, None) == -4   # one head of fp16 V must stay below 2 GiB
+    assert L.int_flash_attn_fwd_half_rect(p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4   # causal with Nk < Nq
     assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
     assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1
 

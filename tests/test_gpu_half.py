@@ -96,6 +96,24 @@ def test_head_counts_and_grid_shapes(ifa, B, H):
     check(ifa, O.reshape(-1, d), x, True, d, label=f"heads {B}x{H}")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,d", [(1, 1000, 128), (128, 512, 128), (100, 333, 128), (256, 1024, 64), (130, 131, 128),
+                                     (64, 2048, 128), (300, 200, 64)])
+def test_rectangular_problems(ifa, Nq, Nk, d, causal):
+    if causal and Nk < Nq:
+        return                                  # refused on the host (tests/test_abi.py)
+    H = 3
+    wq = workloads.custom("t", 1, H, max(Nq, Nk), d, causal, dist="normal", seed=5 * Nq + Nk + d)
+    x = inputs(wq)
+    y = {"Qq": np.ascontiguousarray(x["Qq"][:, :Nq]), "sQ": np.ascontiguousarray(x["sQ"][:, :Nq]),
+         "Kq": np.ascontiguousarray(x["Kq"][:, :Nk]), "sK": np.ascontiguousarray(x["sK"][:, :Nk]),
+         "Vh": np.ascontiguousarray(x["Vh"][:, :Nk])}
+    O = ifa.int_flash_attn_fwd_half(dev(y["Qq"][None]), dev(y["Kq"][None]), dev(y["Vh"][None]), dev(y["sQ"][None]),
+                                    dev(y["sK"][None]), causal=causal, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check(ifa, O.cpu().numpy().reshape(-1, d), y, causal, d, label=f"rect Nq={Nq} Nk={Nk} d={d} causal={causal}")
+
+
 def test_unscaled_scores_and_wide_range(ifa):
     # the paper's literal S = Q K^T (no 1/sqrt(d)): scores of standard deviation ~11, most weights underflow fp16
     w = workloads.custom("t", 1, 4, 512, 128, False, dist="normal", seed=99)

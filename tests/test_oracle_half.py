@@ -121,3 +121,23 @@ def test_row_subset_and_block_size_dependence():
     # unlike Algorithm 1 proper the weights are not on a coarse grid: two block sizes agree to fp16 rounding noise
     other = oracle.int_flash_attn_fwd_half(Qq, Kq, V, sQ, sK, False, 16)["O"]
     assert np.abs(other - full).max() <= 2.0 ** -10 * float(np.abs(V.astype(np.float64)).max())
+
+
+def test_rectangular_rows_are_rows_of_the_square_problem():
+    # rows are independent: the last Nq rows of the square causal problem are the causal rectangular problem
+    rng = np.random.default_rng(66)
+    N, Nq, d = 160, 48, 32
+    Qq, Kq, V, sQ, sK = _problem(rng, 2, N, d, 2.0)
+    pick = (np.arange(2)[:, None] * N + np.arange(N - Nq, N)[None, :]).ravel()
+    for causal in (False, True):
+        full = oracle.int_flash_attn_fwd_half(Qq, Kq, V, sQ, sK, causal, 64)
+        rect = oracle.int_flash_attn_fwd_half(Qq[:, N - Nq:], Kq, V, sQ[:, N - Nq:], sK, causal, 64)
+        for key in ("O", "l", "m"):
+            assert np.array_equal(rect[key], full[key][pick]), key
+    # and against fp64 attention with the library softmax under the shifted mask
+    Nq2 = 40
+    got = oracle.int_flash_attn_fwd_half(Qq[:, :Nq2], Kq, V, sQ[:, :Nq2], sK, True, 32)["O"].reshape(2, Nq2, d)
+    S = np.einsum("hik,hjk->hij", dequant(Qq[:, :Nq2], sQ[:, :Nq2]), dequant(Kq, sK))
+    vis = np.arange(N)[None, :] <= (np.arange(Nq2)[:, None] + (N - Nq2))
+    ref = np.einsum("hij,hjc->hic", scipy.special.softmax(np.where(vis[None], S, -np.inf), axis=-1), V.astype(np.float64))
+    assert np.abs(got - ref).max() <= (2 * 2.0 ** -11 + 1e-5) * float(np.abs(V.astype(np.float64)).max())
