@@ -35,7 +35,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef short s4 __attribute__((ext_vector_type(4)));
 
 constexpr int BCH = 64;       // keys per block of this variant
-constexpr int NT = BCH / 32;  // 32-key tiles per block
+[[maybe_unused]] constexpr int NT = BCH / 32;  // 32-key tiles per block
 
 template <int D> struct SmemH {
     alignas(1024) int8_t k[2][BCH * D];        // K_j int8, row = key, 16-byte slots XOR-swizzled by row
