@@ -280,6 +280,33 @@ def test_rectangular_problems(ifa, Nq, Nk, d, causal):
                          label=f"rect Nq={Nq} Nk={Nk} d={d} causal={causal}")
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 10))
+        Nk = int(rng.integers(1, 700))
+        causal = bool(rng.integers(0, 2))
+        Nq = int(rng.integers(1, Nk + 1)) if causal else int(rng.integers(1, 700))
+        out.append((H, Nq, Nk, d, causal))
+    return out
+
+
+@pytest.mark.parametrize("H,Nq,Nk,d,causal", _random_shapes(24, 2024))
+def test_seeded_random_shapes(ifa, H, Nq, Nk, d, causal):
+    # a fixed, seeded sample of odd shapes: any head count, any Nq, Nk (ragged in both), both head dims, both masks
+    rng = np.random.default_rng(H * 1000003 + Nq * 1009 + Nk)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, max(Nq, Nk), d, score_sigma=float(rng.uniform(0.5, 6.0)))
+    Qq, sQ = np.ascontiguousarray(Qq[:, :Nq]), np.ascontiguousarray(sQ[:, :Nq])
+    Kq, Vq, sK = np.ascontiguousarray(Kq[:, :Nk]), np.ascontiguousarray(Vq[:, :Nk]), np.ascontiguousarray(sK[:, :Nk])
+    O = ifa.int_flash_attn_fwd(dev(Qq[None]), dev(Kq[None]), dev(Vq[None]), dev(sQ[None]), dev(sK[None]), dev(sV[None]),
+                               causal=causal, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), Qq, Kq, Vq, sQ, sK, sV, causal,
+                         label=f"random H={H} Nq={Nq} Nk={Nk} d={d} causal={causal}")
+
+
 def ctypes_ptr(t):
     import ctypes
     return ctypes.c_void_p(t.data_ptr())
