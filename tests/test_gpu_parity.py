@@ -280,6 +280,29 @@ def test_rectangular_problems(ifa, Nq, Nk, d, causal):
                          label=f"rect Nq={Nq} Nk={Nk} d={d} causal={causal}")
 
 
+@pytest.mark.parametrize("dtype", ["float16", "bfloat16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(1, 128), (33, 64), (127, 128), (129, 64), (200, 128), (515, 128)])
+def test_ragged_lengths_with_two_byte_outputs(ifa, N, d, causal, dtype):
+    # 2-byte outputs leave through the staged row-wise store: rows past N must not be written (canaries on both
+    # sides of O) and the values must be the fp32 result rounded once
+    heads = 3
+    w = workloads.custom("t", 1, heads, N, d, causal, dist="normal", seed=17 * N + d)
+    x = quantized_inputs(w, scaled=True)
+    sh = (1, heads, N, d)
+    tdt = getattr(torch, dtype)
+    guard = 256
+    Obuf = torch.full((guard + heads * N + guard, d), 77.0, dtype=tdt, device="cuda")
+    O = Obuf[guard:guard + heads * N].view(sh)
+    args = (dev(x["Qq"].reshape(sh)), dev(x["Kq"].reshape(sh)), dev(x["Vq"].reshape(sh)), dev(x["sQ"].reshape(1, heads, N)),
+            dev(x["sK"].reshape(1, heads, N)), dev(x["sV"].reshape(1, heads)))
+    ifa.int_flash_attn_fwd(*args, causal=causal, out=O)
+    O32 = ifa.int_flash_attn_fwd(*args, causal=causal, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert bool((Obuf[:guard] == 77.0).all()) and bool((Obuf[guard + heads * N:] == 77.0).all())
+    assert torch.equal(O, O32.to(tdt))
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
