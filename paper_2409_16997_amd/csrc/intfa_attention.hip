@@ -39,10 +39,15 @@ namespace {
 using namespace ifa_dev;
 
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
+// Both integer GEMMs start their accumulators at the bit pattern of 1.5 * 2^23 instead of 0: an int32 sum s with
+// |s| < 2^22 then reads, as a float, exactly 1.5 * 2^23 + s, and one fp32 subtraction replaces v_cvt_f32_i32 (which
+// costs twice a subtraction on this chip).  |Q K^T| <= 128 * 128 * 128 = 2^21 and |P V| <= 128 * 127 * 128 < 2^21.
+constexpr int ACC_BIAS_I = 0x4B400000;
+constexpr float ACC_BIAS_F = 12582912.0f;
 [[maybe_unused]] constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
 
 template <int D> struct Smem {
-    alignas(1024) int8_t k[2][BC * D];   // K_j, row = key, 16-byte slots XOR-swizzled by row
+    alignas(4096) int8_t k[2][BC * D];   // K_j, row = key, 16-byte slots XOR-swizzled by row
     alignas(1024) int8_t v[2][BC * D];   // V_j, row = key, 16-byte slots XOR-swizzled by row
     alignas(512) float sk[2][BC];        // s_K of the block
 };
@@ -83,36 +88,52 @@ __device__ __forceinline__ void stage_tile_async(const int8_t *__restrict__ gtil
 
 // Per-lane LDS byte offsets of the MFMA operands inside a K / V tile (tile- and block-independent).
 template <int D> struct LaneOffsets {
-    int k[D / 32];        // A operand of S^T = K Q^T, k-step kk: row r, chunk 2*kk + g   (+ 32*mt*D per key tile)
-    int v[2][D / 32];     // A operand of O^T = V^T P^T: half h (bytes 8h..8h+7), d tile dt (+ 32*mt*D per key tile)
+    // A operand of S^T = K Q^T, k-step kk: row r, chunk 2*kk + g.  The swizzle is an XOR on the chunk index and
+    // 2*kk + g = 2*kk ^ g, so the offset of step kk is k0 ^ (32*kk): one register serves all steps (+ 32*mt*D per
+    // key tile, an immediate).
+    unsigned k0;
+    // A operand of O^T = V^T P^T, d tile dt, bytes 0..7 of the operand: v0 ^ (32*dt) by the same argument; bytes
+    // 8..15 come from the key 16 rows further on, which the swizzle does not see: + 16*D (+ 32*mt*D per key tile).
+    unsigned v0;
     int sk;               // first of this lane's s_K values in a 32-key tile (+ 128*mt + 32*vq bytes)
-    unsigned gk[D / 32];  // staging: byte offset inside the K tile in HBM of the chunk this lane moves in piece i
-    unsigned gv[D / 32];  // same for the V tile
+    // staging: byte offset inside the K / V tile in HBM of the chunk this lane moves in piece i of its wavefront.
+    // Piece i covers rows 1024 i / D further on, and the row bits the swizzles look at do not change with i except
+    // one bit of the V swizzle (D = 128) that follows the parity of i: offset(i) = gk + 1024 i for K and
+    // gv[i & 1] + 1024 (i - (i & 1)) for V, the multiples of 1024 going into the scalar offset of the copy.
+    unsigned gk;
+    unsigned gv[2];
     __device__ __forceinline__ LaneOffsets(int lane, int wave) {
         const int r = lane & 31, g = lane >> 5;
         constexpr int CH = D / 16, ITER = D / 32;
 #pragma unroll
-        for (int i = 0; i < ITER; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const int p = (wave * ITER + i) * 64 + lane, row = p / CH, slot = p % CH;
-            gk[i] = row * D + 16 * (slot ^ k_swz<D>(row));
+            if (i == 0) gk = row * D + 16 * (slot ^ k_swz<D>(row));
             gv[i] = row * D + 16 * (slot ^ v_swz<D>(row));
         }
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) k[kk] = r * D + (((2 * kk + g) ^ k_swz<D>(r)) * 16);
+        k0 = r * D + ((g ^ k_swz<D>(r)) * 16);
         // transposing read: 16-lane group G = lane / 16 serves d columns 16*(G%2) .. +15 of the tile and key
         // half g = G / 2; lane i of the group addresses row (i / 2) of its 8 keys, byte half (i % 2).
         const int i = lane & 15, G = lane >> 4, kidx = i >> 1, par = i & 1;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int b = 8 * h + kidx;
-            const int key = 8 * (b >> 2) + 4 * g + (b & 3);          // accumulator row order
-#pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt)
-                v[h][dt] = key * D + (((2 * dt + (G & 1)) ^ v_swz<D>(key)) * 16) + 8 * par;
-        }
+        const int key = 8 * (kidx >> 2) + 4 * g + (kidx & 3);        // accumulator row order
+        v0 = key * D + (((G & 1) ^ v_swz<D>(key)) * 16) + 8 * par;
         sk = 16 * g;
     }
 };
+
+// LDS addresses of the operands.  Tile bases are multiples of 4096 and the lane offsets are below 4096, so the XOR
+// that selects the step also adds the base: one vector instruction per address, the tile base and the step
+// combined on the scalar side.
+__device__ __forceinline__ lds_ptr lds_xor(lds_ptr base, unsigned step, unsigned lane_off) {
+    const unsigned a = (static_cast<unsigned>(reinterpret_cast<uintptr_t>(base)) + step) ^ lane_off;
+    return reinterpret_cast<lds_ptr>(static_cast<uintptr_t>(a));
+}
+template <int D> __device__ __forceinline__ lds_ptr k_operand(lds_ptr ks, const LaneOffsets<D> &lo, int kk) {
+    return lds_xor(ks, 32 * kk, lo.k0);
+}
+template <int D> __device__ __forceinline__ lds_ptr v_operand(lds_ptr vs, const LaneOffsets<D> &lo, int dt) {
+    return lds_xor(vs, 32 * dt, lo.v0);
+}
 
 // What the next key block needs staged.  The copies are buffer_load_dwordx4 ... lds: the tensor's base and
 // size sit in a scalar buffer resource, the block offset in a scalar register and the lane's chunk offset in
@@ -137,11 +158,11 @@ struct Prefetch {
 
 template <int D>
 __device__ __forceinline__ void prefetch_k_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on) lds_copy16(nx.k, nx.lk + (wave * (D / 32) + i) * 1024, lo.gk[i], nx.koff);
+    if (nx.on) lds_copy16(nx.k, nx.lk + (wave * (D / 32) + i) * 1024, lo.gk, nx.koff + 1024 * i);
 }
 template <int D>
 __device__ __forceinline__ void prefetch_v_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on) lds_copy16(nx.v, nx.lv + (wave * (D / 32) + i) * 1024, lo.gv[i], nx.koff);
+    if (nx.on) lds_copy16(nx.v, nx.lv + (wave * (D / 32) + i) * 1024, lo.gv[i & 1], nx.koff + 1024 * (i - (i & 1)));
 }
 __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int lane) {
     // 2 x 64 lanes x 4 bytes = the 128 scales of the block, by wavefronts 2 and 3.  Dword copies: a head's
@@ -156,7 +177,7 @@ __device__ __forceinline__ v16i gemm_kq_tile(lds_ptr ks, const LaneOffsets<D> &l
     v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) {
-        const v4i a = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
+        const v4i a = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * mt * D);
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[kk], acc, 0, 0, 0);
     }
     return acc;
@@ -165,8 +186,8 @@ __device__ __forceinline__ v16i gemm_kq_tile(lds_ptr ks, const LaneOffsets<D> &l
 // one k-step (32 keys of tile mt) of O^T tile dt
 template <int D>
 __device__ __forceinline__ v16i gemm_vp_step(lds_ptr vs, const LaneOffsets<D> &lo, v4i p, int dt, int mt, v16i acc) {
-    const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[0][dt] + 32 * mt * D));
-    const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[1][dt] + 32 * mt * D));
+    const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * mt * D));
+    const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * mt * D));
     const v4i a = {t0[0], t0[1], t1[0], t1[1]};
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, p, acc, 0, 0, 0);
 }
@@ -192,23 +213,22 @@ template <int D> struct RowState {
 template <int D, bool DIAG, bool VB>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile,
-                                              int g, float oscale, const Prefetch &nx, RowState<D> &st) {
+                                              int g, float oscale, const Prefetch &nx, const v16i &bias, RowState<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
-    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
 
-    v4i kop[2][KS];
-    v4f skr[2][4];
+    v4i kop[KS];
+    v4f skr[4];
     float a[4][16];
     float bmax = -INFINITY;
 
-    auto load_k = [&](int buf, int mt) {
+    auto load_k = [&](int mt) {
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) kop[buf][kk] = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
+        for (int kk = 0; kk < KS; ++kk) kop[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * mt * D);
     };
-    auto load_sk = [&](int buf, int mt) {
+    auto load_sk = [&](int mt) {
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) skr[buf][vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
+        for (int vq = 0; vq < 4; ++vq) skr[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
     };
     // line 9, fp32 part: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
     auto scale_tile = [&](int mt, const v16i &s, const v4f (&skv)[4]) {
@@ -216,28 +236,29 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float x = static_cast<float>(s[4 * vq + e]) * skv[vq][e];
+                float x = (__int_as_float(s[4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
                 if (DIAG && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
     };
 
-    // ---- S^T = K Q^T, tile by tile; tile mt-1 is scaled while tile mt is in the matrix pipe
+    // ---- S^T = K Q^T, tile by tile; tile mt-1 is scaled while tile mt is in the matrix pipe.  One register set
+    // each for the K operands and the scales: the operands of tile mt+1 are requested right after the MFMAs of
+    // tile mt have been issued (they read their operands at issue), the scales of tile mt-1 just before them.
     v16i sacc[2];
-    load_k(0, 0);
-    load_sk(0, 0);
+    load_k(0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         if (mt <= last) {
-            if (mt + 1 <= last) load_k((mt + 1) & 1, mt + 1);
-            sacc[mt & 1] = zero;
+            if (mt > 0) load_sk(mt - 1);
+            sacc[mt & 1] = bias;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk)
-                sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt & 1], 0, 0, 0);
-            if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr[(mt - 1) & 1]);
-            // the scales of tile mt+1 reuse the registers tile mt-1's scales have just left
-            if (mt + 1 <= last) load_sk((mt + 1) & 1, mt + 1);
+                sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[kk], qf[kk], sacc[mt & 1], 0, 0, 0);
+            if (mt + 1 <= last) load_k(mt + 1);                  // into the registers the MFMAs above have read
+            if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr);
+            if (mt == last) load_sk(mt);
             if (!DIAG && mt < KS) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
         } else {
 #pragma unroll
@@ -250,8 +271,8 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
             if (mt <= last) {
-                const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[0][dt] + 32 * mt * D));
-                const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(vs + lo.v[1][dt] + 32 * mt * D));
+                const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * mt * D));
+                const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * mt * D));
                 vop[buf][mt] = v4i{t0[0], t0[1], t1[0], t1[1]};
             }
         }
@@ -259,7 +280,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     load_v(0, 0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
-        if (mt == last) scale_tile(mt, sacc[mt & 1], skr[mt & 1]);
+        if (mt == last) scale_tile(mt, sacc[mt & 1], skr);
 
     // line 10
     bmax = pair_max(bmax);
@@ -298,12 +319,14 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     const float alpha_o = VB ? alpha * oscale : alpha;
     auto fold_o = [&](int dt, const v16i &pv) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -static_cast<float>(pv[v]));
+        for (int v = 0; v < 16; ++v)
+            st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(__int_as_float(pv[v]) - ACC_BIAS_F));
+
     };
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
         if (dt + 1 < DT) load_v((dt + 1) & 1, dt + 1);
-        pacc[dt & 1] = zero;
+        pacc[dt & 1] = bias;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
             if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
@@ -366,6 +389,11 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         prefetch_sk(first, wave, lane);
     }
 
+    v16i bias;                                                   // 16 registers that stay constant: the MFMAs never write them
+#pragma unroll
+    for (int v = 0; v < 16; ++v) bias[v] = ACC_BIAS_I;
+    asm volatile("" : "+v"(bias));                               // opaque: kept in registers, not re-materialised per use
+
     // line 6
     RowState<D> st;
     st.m2 = -INFINITY;
@@ -387,13 +415,13 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     float sv_prev = 1.0f;
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
-        const float sv_j = VB ? sVh[jb] : 1.0f;
-        const float oscale = VB ? sv_prev / sv_j : 1.0f;
+        const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
+        const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
         sv_prev = sv_j;
         const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
         const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D,
                              skbuf + nxt * BC * 4, jb + 1 < nblocks};
-        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, oscale, pf, st);
+        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, oscale, pf, bias, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
@@ -409,10 +437,10 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const int wlim = CAUSAL ? min(first_q + 32 * wave + 31 + shift - j0, tail) : tail;
         if (wlim >= 0) {                                         // wave-uniform: this wavefront sees part of the block
             const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
-            const float sv_j = VB ? sVh[jb] : 1.0f;
-            const float oscale = VB ? sv_prev / sv_j : 1.0f;
+            const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
+            const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
             sv_prev = sv_j;
-            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), g, oscale, none, st);
+            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), g, oscale, none, bias, st);
         }
     };
     if (nfull < nblocks) {

@@ -72,6 +72,11 @@ __device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigne
 // every outstanding memory operation of this wavefront has completed (vmcnt = expcnt = lgkmcnt = 0)
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
+// a value that is the same in every lane, moved to a scalar register
+__device__ __forceinline__ float uniform(float x) {
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
+}
+
 // max over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
 __device__ __forceinline__ float pair_max(float x) {
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
