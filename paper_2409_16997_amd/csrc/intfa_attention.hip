@@ -39,11 +39,6 @@ namespace {
 using namespace ifa_dev;
 
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
-// Both integer GEMMs start their accumulators at the bit pattern of 1.5 * 2^23 instead of 0: an int32 sum s with
-// |s| < 2^22 then reads, as a float, exactly 1.5 * 2^23 + s, and one fp32 subtraction replaces v_cvt_f32_i32 (which
-// costs twice a subtraction on this chip).  |Q K^T| <= 128 * 128 * 128 = 2^21 and |P V| <= 128 * 127 * 128 < 2^21.
-constexpr int ACC_BIAS_I = 0x4B400000;
-constexpr float ACC_BIAS_F = 12582912.0f;
 [[maybe_unused]] constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
 
 template <int D> struct Smem {
@@ -121,13 +116,6 @@ template <int D> struct LaneOffsets {
     }
 };
 
-// LDS addresses of the operands.  Tile bases are multiples of 4096 and the lane offsets are below 4096, so the XOR
-// that selects the step also adds the base: one vector instruction per address, the tile base and the step
-// combined on the scalar side.
-__device__ __forceinline__ lds_ptr lds_xor(lds_ptr base, unsigned step, unsigned lane_off) {
-    const unsigned a = (static_cast<unsigned>(reinterpret_cast<uintptr_t>(base)) + step) ^ lane_off;
-    return reinterpret_cast<lds_ptr>(static_cast<uintptr_t>(a));
-}
 template <int D> __device__ __forceinline__ lds_ptr k_operand(lds_ptr ks, const LaneOffsets<D> &lo, int kk) {
     return lds_xor(ks, 32 * kk, lo.k0);
 }
@@ -153,21 +141,24 @@ struct Prefetch {
     BufRsrc k, v, sk;                // one head's K [N, d], V [N, d] int8 and s_K [N] fp32
     int koff, skoff;                 // byte offset of the next block inside K (= inside V) and inside s_K
     lds_ptr lk, lv, lsk;             // LDS destinations (tile bases)
-    bool on;                         // false: nothing follows
 };
+// Block offset of a request that must fetch nothing (no block follows): past the end of any tensor, so that every
+// lane is out of range -- the scalar offset takes part in the range check (probed on this chip) -- and the copy
+// moves no data.  Cheaper than a branch around each copy: the block stays one basic block for the scheduler.
+constexpr int NOWHERE = 0x7fff0000;
 
 template <int D>
 __device__ __forceinline__ void prefetch_k_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on) lds_copy16(nx.k, nx.lk + (wave * (D / 32) + i) * 1024, lo.gk, nx.koff + 1024 * i);
+    lds_copy16(nx.k, nx.lk + (wave * (D / 32) + i) * 1024, lo.gk, nx.koff + 1024 * i);
 }
 template <int D>
 __device__ __forceinline__ void prefetch_v_piece(const Prefetch &nx, const LaneOffsets<D> &lo, int wave, int i) {
-    if (nx.on) lds_copy16(nx.v, nx.lv + (wave * (D / 32) + i) * 1024, lo.gv[i & 1], nx.koff + 1024 * (i - (i & 1)));
+    lds_copy16(nx.v, nx.lv + (wave * (D / 32) + i) * 1024, lo.gv[i & 1], nx.koff + 1024 * (i - (i & 1)));
 }
 __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int lane) {
     // 2 x 64 lanes x 4 bytes = the 128 scales of the block, by wavefronts 2 and 3.  Dword copies: a head's
     // scales start at an arbitrary 4-byte boundary when N is not a multiple of 4.
-    if (nx.on && wave >= 2) lds_copy4(nx.sk, nx.lsk + 256 * (wave - 2), 4 * lane + 256 * (wave - 2), nx.skoff);
+    if (wave >= 2) lds_copy4(nx.sk, nx.lsk + 256 * (wave - 2), 4 * lane + 256 * (wave - 2), nx.skoff);
 }
 
 // ---- the two MFMA tile products -----------------------------------------------------------------
@@ -383,7 +374,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const float sq2 = sQ[qrow] * LOG2E;
     const LaneOffsets<D> lo(lane, wave);
     {                                                            // line 8 for block 0
-        const Prefetch first = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, true};
+        const Prefetch first = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf};
 #pragma unroll
         for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(first, lo, wave, i); prefetch_v_piece<D>(first, lo, wave, i); }
         prefetch_sk(first, wave, lane);
@@ -419,8 +410,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
         sv_prev = sv_j;
         const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
-        const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D,
-                             skbuf + nxt * BC * 4, jb + 1 < nblocks};
+        const bool more = jb + 1 < nblocks;
+        const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
+                             vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
         process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, oscale, pf, bias, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
@@ -436,7 +428,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;
         const int wlim = CAUSAL ? min(first_q + 32 * wave + 31 + shift - j0, tail) : tail;
         if (wlim >= 0) {                                         // wave-uniform: this wavefront sees part of the block
-            const Prefetch none = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf, false};
+            const Prefetch none = {rK, rV, rSK, NOWHERE, NOWHERE, kbuf, vbuf, skbuf};   // masked blocks request nothing
             const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
             const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
             sv_prev = sv_j;
@@ -447,7 +439,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const bool second = nfull + 1 < nblocks;
         if (second) {                                            // line 8 for the second masked block
             const int nxt = (nfull & 1) ^ 1, j1 = (nfull + 1) * BC;
-            const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D, skbuf + nxt * BC * 4, true};
+            const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
 #pragma unroll
             for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(pf, lo, wave, i); prefetch_v_piece<D>(pf, lo, wave, i); }
             prefetch_sk(pf, wave, lane);
@@ -583,7 +575,8 @@ int fwd_entry(const signed char *Q_i8, const signed char *K_i8, const signed cha
     if (causal && Nk < Nq) return IFA_ERR_UNSUPPORTED;           // a query with no visible key
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
-    if (static_cast<long>(N) * d > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
+    if (static_cast<long>(N) * d > 0x7ff00000L ||   // a head's K (or V) stays below NOWHERE
+         heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
         (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) ||
         (reinterpret_cast<uintptr_t>(s_V) & 3))

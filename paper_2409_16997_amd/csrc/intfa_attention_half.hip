@@ -38,7 +38,7 @@ constexpr int BCH = 64;       // keys per block of this variant
 [[maybe_unused]] constexpr int NT = BCH / 32;  // 32-key tiles per block
 
 template <int D> struct SmemH {
-    alignas(1024) int8_t k[2][BCH * D];        // K_j int8, row = key, 16-byte slots XOR-swizzled by row
+    alignas(4096) int8_t k[2][BCH * D];        // K_j int8, row = key, 16-byte slots XOR-swizzled by row
     alignas(1024) int8_t v[2][BCH * D * 2];    // V_j fp16, row = key (2 D bytes), 64-byte chunks XOR-swizzled by row
     alignas(256) float sk[2][BCH];             // s_K of the block
 };
@@ -55,33 +55,30 @@ template <int D> __device__ __forceinline__ int vh_swz(int row) {
 
 template <int D> struct LaneOffsetsH {
     static constexpr int KS = D / 32, DT = D / 32, KP = D / 64, VP = D / 32;
-    int k[KS];            // A operand of S^T: row r, 16-byte chunk 2*kk + g            (+ 32*mt*D per key tile)
-    int v[2][DT];         // A operand of O^T: keys 8h + 4g + (i/4) of a 16-key step, d tile dt (+ (32*mt + 16*s)*2D)
-    unsigned gk[KP];      // staging: byte offset inside the K block in HBM of the chunk this lane moves in piece i
-    unsigned gv[VP];      // same for the V block
+    // A operand of S^T: row r, 16-byte chunk 2*kk + g.  The swizzle XORs the chunk index and 2*kk + g = 2*kk ^ g,
+    // so step kk is at k0 ^ (32*kk)   (+ 32*mt*D per key tile, an immediate)
+    unsigned k0;
+    // A operand of O^T: keys 4g + (i/4) of a 16-key step, d tile dt at v0 ^ (64*dt); the keys 8 further on, which the
+    // swizzle does not see, at + 8 * 2D   (+ (32*mt + 16*s) * 2D per step)
+    unsigned v0;
+    // staging: byte offset inside the K / V block in HBM of the chunk this lane moves in piece 0 of its wavefront;
+    // piece i is 1024 bytes further on (whole rows, which the swizzles do not see)
+    unsigned gk, gv;
     __device__ __forceinline__ LaneOffsetsH(int lane, int wave) {
         const int r = lane & 31, g = lane >> 5;
         constexpr int CH = D / 16, CHV = D / 8;      // 16-byte slots per K row / per V row
-#pragma unroll
-        for (int i = 0; i < KP; ++i) {
-            const int p = (wave * KP + i) * 64 + lane, row = p / CH, slot = p % CH;
-            gk[i] = row * D + 16 * (slot ^ kh_swz<D>(row));
+        {
+            const int p = wave * KP * 64 + lane, row = p / CH, slot = p % CH;      // a piece is 1024 / D >= 8 rows
+            gk = row * D + 16 * (slot ^ kh_swz<D>(row));
         }
-#pragma unroll
-        for (int i = 0; i < VP; ++i) {
-            const int p = (wave * VP + i) * 64 + lane, row = p / CHV, slot = p % CHV;
-            gv[i] = row * (2 * D) + 16 * (slot ^ (vh_swz<D>(row) << 2));
+        {
+            const int p = wave * VP * 64 + lane, row = p / CHV, slot = p % CHV;    // a piece is 512 / D >= 4 rows
+            gv = row * (2 * D) + 16 * (slot ^ (vh_swz<D>(row) << 2));
         }
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) k[kk] = r * D + (((2 * kk + g) ^ kh_swz<D>(r)) * 16);
+        k0 = r * D + ((g ^ kh_swz<D>(r)) * 16);
         const int i = lane & 15, G = lane >> 4, kq = i >> 2, j = i & 3;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int key = 8 * h + 4 * g + kq;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                v[h][dt] = key * (2 * D) + ((dt ^ vh_swz<D>(key)) * 64) + 32 * (G & 1) + 8 * j;
-        }
+        const int key = 4 * g + kq;
+        v0 = key * (2 * D) + (vh_swz<D>(key) * 64) + 32 * (G & 1) + 8 * j;
     }
 };
 
@@ -89,19 +86,19 @@ struct PrefetchH {
     BufRsrc k, v, sk;                // one head's K [N, d] int8, V [N, d] fp16 and s_K [N] fp32
     int koff, voff, skoff;           // byte offsets of the next block inside K, V and s_K
     lds_ptr lk, lv, lsk;             // LDS destinations
-    bool on;                         // false: nothing follows
 };
+// Block offset of a request that must fetch nothing (no block follows): past the end of any tensor, so every lane
+// is out of range (the scalar offset takes part in the range check) and the copy moves no data.
+constexpr int NOWHERE_H = 0x7fff0000;
 
 template <int D>
 __device__ __forceinline__ void prefetch_block(const PrefetchH &nx, const LaneOffsetsH<D> &lo, int wave, int lane) {
     constexpr int KP = D / 64, VP = D / 32;
-    if (nx.on) {
 #pragma unroll
-        for (int i = 0; i < KP; ++i) lds_copy16(nx.k, nx.lk + (wave * KP + i) * 1024, lo.gk[i], nx.koff);
+    for (int i = 0; i < KP; ++i) lds_copy16(nx.k, nx.lk + (wave * KP + i) * 1024, lo.gk, nx.koff + 1024 * i);
 #pragma unroll
-        for (int i = 0; i < VP; ++i) lds_copy16(nx.v, nx.lv + (wave * VP + i) * 1024, lo.gv[i], nx.voff);
-        if (wave == 3) lds_copy4(nx.sk, nx.lsk, 4 * lane, nx.skoff);   // 64 lanes x 4 bytes = the 64 scales of the block
-    }
+    for (int i = 0; i < VP; ++i) lds_copy16(nx.v, nx.lv + (wave * VP + i) * 1024, lo.gv, nx.voff + 1024 * i);
+    if (wave == 3) lds_copy4(nx.sk, nx.lsk, 4 * lane, nx.skoff);       // 64 lanes x 4 bytes = the 64 scales of the block
 }
 
 template <int D> struct RowStateH {
@@ -116,10 +113,9 @@ template <int D> struct RowStateH {
 template <int D, bool MASKED>
 __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsetsH<D> &lo,
                                                    const v4i (&qf)[D / 32], float sq2, int klimit, int last_tile, int g,
-                                                   RowStateH<D> &st) {
+                                                   const v16i &bias, RowStateH<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = MASKED ? last_tile : NT - 1;
-    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     float a[NT][16];
     float bmax = -INFINITY;
 
@@ -129,7 +125,7 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
     v4f skr[2][4];
     auto load_k = [&](int buf, int mt) {
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) kop[buf][kk] = *reinterpret_cast<LDS_AS const v4i *>(ks + lo.k[kk] + 32 * mt * D);
+        for (int kk = 0; kk < KS; ++kk) kop[buf][kk] = *reinterpret_cast<LDS_AS const v4i *>(lds_xor(ks, 32 * kk, lo.k0) + 32 * mt * D);
     };
     auto load_sk = [&](int buf, int mt) {
 #pragma unroll
@@ -140,7 +136,7 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float x = static_cast<float>(acc[4 * vq + e]) * skv[vq][e];
+                float x = (__int_as_float(acc[4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
                 if (MASKED && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
@@ -155,8 +151,8 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const int koff = (32 * mt + 16 * s) * (2 * D);
-                    const h4 t0 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[0][dt] + koff)));
-                    const h4 t1 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(vs + lo.v[1][dt] + koff)));
+                    const h4 t0 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(lds_xor(vs, 64 * dt, lo.v0) + koff)));
+                    const h4 t1 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(lds_xor(vs, 64 * dt, lo.v0) + 8 * (2 * D) + koff)));
                     vop[buf][2 * mt + s] = h8{t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
                 }
             }
@@ -170,7 +166,7 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
     for (int mt = 0; mt < NT; ++mt) {
         if (mt <= last) {
             if (mt + 1 <= last) load_k((mt + 1) & 1, mt + 1);
-            sacc[mt & 1] = zero;
+            sacc[mt & 1] = bias;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk)
                 sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt & 1], 0, 0, 0);
@@ -276,9 +272,14 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     const float sq2 = sQ[qrow] * LOG2E;
     const LaneOffsetsH<D> lo(lane, wave);
     {
-        const PrefetchH first = {rK, rV, rSK, 0, 0, 0, kbuf, vbuf, skbuf, true};
+        const PrefetchH first = {rK, rV, rSK, 0, 0, 0, kbuf, vbuf, skbuf};
         prefetch_block<D>(first, lo, wave, lane);
     }
+
+    v16i bias;                                                   // constant registers the S^T accumulators start from
+#pragma unroll
+    for (int v = 0; v < 16; ++v) bias[v] = ACC_BIAS_I;
+    asm volatile("" : "+v"(bias));                               // opaque: kept in registers, not re-materialised per use
 
     RowStateH<D> st;
     st.m2 = -INFINITY;
@@ -297,14 +298,15 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     const int wave_last_q = first_q + 32 * wave + 31;            // last query of this wavefront
     auto next_block = [&](int jb) {                              // what block jb + 1 needs staged, into the other buffers
         const int nxt = (jb & 1) ^ 1, j1 = (jb + 1) * BCH;
-        return PrefetchH{rK, rV, rSK, j1 * D, j1 * D * 2, j1 * 4, kbuf + nxt * BCH * D, vbuf + nxt * BCH * D * 2,
-                         skbuf + nxt * BCH * 4, jb + 1 < nblocks};
+        const bool more = jb + 1 < nblocks;
+        return PrefetchH{rK, rV, rSK, more ? j1 * D : NOWHERE_H, more ? j1 * D * 2 : NOWHERE_H, more ? j1 * 4 : NOWHERE_H,
+                         kbuf + nxt * BCH * D, vbuf + nxt * BCH * D * 2, skbuf + nxt * BCH * 4};
     };
     for (int jb = 0; jb < nfull; ++jb) {
         const int cur = jb & 1;
         prefetch_block<D>(next_block(jb), lo, wave, lane);
         process_block_half<D, false>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
-                                     0, NT - 1, g, st);
+                                     0, NT - 1, g, bias, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
         const int last_tile = wlim < 0 ? -1 : min(NT - 1, wlim >> 5);
         if (last_tile >= 0)                                                        // wave-uniform
             process_block_half<D, true>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
-                                        klimit, last_tile, g, st);
+                                        klimit, last_tile, g, bias, st);
         wait_all_memory();
         __syncthreads();
     }
@@ -374,7 +376,7 @@ int half_entry(const signed char *Q_i8, const signed char *K_i8, const void *V_f
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 64 && d != 128) return IFA_ERR_UNSUPPORTED;
     if (causal && Nk < Nq) return IFA_ERR_UNSUPPORTED;           // a query with no visible key
-    if (static_cast<long>(N) * d * 2 > 0x7fffffffL || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
+    if (static_cast<long>(N) * d * 2 > 0x7ff00000L || heads * ((N + BR - 1) / BR) > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_f16) || !ifa_aligned16(O) ||
         (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3))
         return IFA_ERR_UNSUPPORTED;

@@ -22,6 +22,12 @@ constexpr int BR = 128;       // query rows per workgroup
 constexpr int THREADS = 256;  // 4 wavefronts x 32 query rows
 constexpr float LOG2E = 1.44269504088896340736f;
 
+// The integer GEMMs start their accumulators at the bit pattern of 1.5 * 2^23 instead of 0: an int32 sum s with
+// |s| < 2^22 then reads, as a float, exactly 1.5 * 2^23 + s, and one fp32 subtraction replaces v_cvt_f32_i32 (which
+// costs twice a subtraction on this chip).  |Q K^T| <= 128 * 128 * 128 = 2^21 and |P V| <= 128 * 127 * 128 < 2^21.
+constexpr int ACC_BIAS_I = 0x4B400000;
+constexpr float ACC_BIAS_F = 12582912.0f;
+
 // Heads an XCD works on at a time: 4 heads of K and V (N = 4096, d = 128: 4 MB) fit its 4 MB L2, and a group
 // of 4 gave the shortest causal run of the group sizes 1, 2, 4, 8, 16 measured on MI355X.
 constexpr int HEAD_GROUP = 4;
@@ -68,6 +74,14 @@ __device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigne
                  :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
 }
 #pragma clang diagnostic pop
+
+// LDS address of an MFMA operand: (tile base + step) ^ lane offset.  Tile bases are multiples of 4096 and the lane
+// offsets are below 4096, so the XOR that selects the step also adds the base: one vector instruction per address,
+// the tile base and the step combined on the scalar side.
+__device__ __forceinline__ lds_ptr lds_xor(lds_ptr base, unsigned step, unsigned lane_off) {
+    const unsigned a = (static_cast<unsigned>(reinterpret_cast<uintptr_t>(base)) + step) ^ lane_off;
+    return reinterpret_cast<lds_ptr>(static_cast<uintptr_t>(a));
+}
 
 // every outstanding memory operation of this wavefront has completed (vmcnt = expcnt = lgkmcnt = 0)
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
