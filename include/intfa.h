@@ -99,8 +99,8 @@ int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d,
  *   O                  [B, H, N, d] out, fp16 for int_flash_attn_fwd, o_dtype for the _ex form
  * There is no softmax scale: the paper's S has none.  A caller that wants 1/sqrt(d) multiplies
  * s_Q by it (exact by the linearity remark of Section 3.2).
- * Supported: d in {64, 128}; any N >= 1 with N*d < 2^31 (keys at or beyond N are masked in the last,
- * ragged key block; rows at or beyond N are not written); B*H*N*d < 2^40.
+ * Supported: d in {64, 128}; any N >= 1 with N*d <= 0x7ff00000 (just under 2^31); keys at or beyond N are
+ * masked in the last, ragged key block and rows at or beyond N are not written; B*H*N*d < 2^40.
  */
 int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                        const float *s_Q, const float *s_K, const float *s_V,
@@ -153,7 +153,7 @@ int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, 
  * over key blocks of ifa_block_cols_half() keys in ascending order.
  *   Q_i8, K_i8 [B, H, N, d] int8;  s_Q, s_K [B, H, N] fp32, strictly positive;  V_f16 [B, H, N, d] fp16 as the
  *   caller has it (not quantized, no s_V);  O [B, H, N, d] of o_dtype.
- * Supported: d in {64, 128}; any N >= 1 with 2*N*d < 2^31.  Same error rules as int_flash_attn_fwd_ex.
+ * Supported: d in {64, 128}; any N >= 1 with 2*N*d <= 0x7ff00000 (just under 2^31).  Same error rules as int_flash_attn_fwd_ex.
  */
 int int_flash_attn_fwd_half(const signed char *Q_i8, const signed char *K_i8, const void *V_f16,
                             const float *s_Q, const float *s_K,

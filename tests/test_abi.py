@@ -67,6 +67,7 @@ def test_argument_validation_happens_on_the_host(L):
     assert f(p, p, p, p, p, p, 1, 1, 128, 96, 0, *ok_tail) == -4      # head dim not built
     assert f(p, p, p, p, p, p, 1, 1, 1 << 30, 128, 0, *ok_tail) == -4  # one head must stay below 2 GiB
     assert f(odd, p, p, p, p, p, 1, 1, 128, 128, 0, *ok_tail) == -4   # misaligned
+    assert f(p, p, p, p, p, p, 1, 1, 0x7ff00000 // 128 + 1, 128, 0, *ok_tail) == -4   # first N past the per-head limit
     assert L.int_flash_attn_fwd(null, p, p, p, p, p, 1, 1, 128, 128, 0, p) == -1
     q = L.quantize_tokenwise
     assert q(null, 1, 10, 128, p, p) == -1
@@ -93,6 +94,7 @@ def test_argument_validation_happens_on_the_host(L):
     assert hf(p, p, null, p, p, 1, 1, 128, 128, 0, p, 1, None) == -1 and hf(p, p, p, p, p, 1, 0, 128, 128, 0, p, 1, None) == -2
     assert hf(p, p, p, p, p, 1, 1, 128, 128, 0, p, -1, None) == -3 and hf(p, p, p, p, p, 1, 1, 128, 256, 0, p, 1, None) == -4
     assert hf(p, p, p, p, p, 1, 1, 1 << 29, 128, 0, p, 1, None) == -4   # one head of fp16 V must stay below 2 GiB
+    assert hf(p, p, p, p, p, 1, 1, 0x7ff00000 // 256 + 1, 128, 0, p, 1, None) == -4   # first N past that limit
     assert L.int_flash_attn_fwd_half_rect(p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4   # causal with Nk < Nq
     assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
     assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1
