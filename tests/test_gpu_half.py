@@ -122,6 +122,25 @@ def test_unscaled_scores_and_wide_range(ifa):
     check(ifa, O.reshape(-1, 128), x, False, 128, label="unscaled")
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_score_accumulator_extremes(ifa, d):
+    # Q, K entries all -128 or 127 with keys that repeat or negate a query's sign pattern: Q K^T reaches
+    # +-d * 128 * 128, the ends of the range the kernel's accumulators have to represent exactly.
+    rng = np.random.default_rng(78 + d)
+    heads, N = 2, 256
+    pick = lambda shape: np.where(rng.random(shape) < 0.5, -128, 127).astype(np.int8)
+    Qq, Kq = pick((heads, N, d)), pick((heads, N, d))
+    Qq[:, 5] = -128; Kq[:, 9] = -128; Kq[:, 10] = 127
+    Kq[:, 20:40] = Qq[:, 200:220]
+    Kq[:, 100:110] = np.where(Qq[:, 60:70] < 0, 127, -128)
+    span = 6.0 / (d * 128.0 * 128.0)
+    x = {"Qq": Qq, "Kq": Kq, "Vh": rng.standard_normal((heads, N, d)).astype(np.float16),
+         "sQ": np.full((heads, N), np.sqrt(span), np.float32), "sK": np.full((heads, N), np.sqrt(span), np.float32)}
+    for causal in (False, True):
+        O = run(ifa, x, 1, heads, N, d, causal).cpu().numpy()
+        check(ifa, O.reshape(-1, d), x, causal, d, label=f"extremes d={d} causal={causal}")
+
+
 def test_degenerate_inputs(ifa):
     B, H, N, d = 1, 2, 256, 128
     rng = np.random.default_rng(5)

@@ -359,6 +359,33 @@ def test_random_int8_grid_inputs_wide_scores(ifa, causal):
         check_against_oracle(ifa, O.reshape(-1, 128), Qq, Kq, Vq, sQ, sK, sV, causal, label=f"int8 sigma={sigma}")
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("causal", [False, True])
+def test_accumulator_extremes_through_the_fused_kernel(ifa, d, causal):
+    # Every entry is -128 or 127 and some keys repeat (or negate) a query's sign pattern, so Q K^T reaches
+    # +-d * 128 * 128 (2^21 at d = 128) and, with V = -128 columns under flat rows, P V reaches -127 * 128 * B_c:
+    # the int32 sums at the ends of their range must still come out exact.
+    rng = np.random.default_rng(77 + d)
+    heads, N = 2, 384
+    pick = lambda shape: np.where(rng.random(shape) < 0.5, -128, 127).astype(np.int8)
+    Qq, Kq, Vq = pick((heads, N, d)), pick((heads, N, d)), pick((heads, N, d))
+    Qq[:, 5] = -128; Kq[:, 9] = -128                           # score of (5, 9): d * 128 * 128, the largest possible
+    Kq[:, 10] = 127                                            # score of (5, 10): -d * 128 * 127
+    Kq[:, 20:40] = Qq[:, 200:220]                              # same sign pattern: large positive
+    Kq[:, 300:310] = np.where(Qq[:, 100:110] < 0, 127, -128)   # opposite pattern: large negative
+    Qq[:, 130:140] = 0                                         # flat rows: every P is 127
+    Vq[:, :, 3] = -128; Vq[:, :, 4] = 127
+    span = 6.0 / (d * 128.0 * 128.0)                           # scores within +-6
+    sQ = np.full((heads, N), np.sqrt(span), np.float32) * rng.uniform(0.9, 1.1, (heads, N)).astype(np.float32)
+    sK = np.full((heads, N), np.sqrt(span), np.float32) * rng.uniform(0.9, 1.1, (heads, N)).astype(np.float32)
+    sV = np.array([0.01, 0.02], np.float32)
+    O = run_gpu(ifa, Qq, Kq, Vq, sQ, sK, sV, 1, heads, causal).cpu().numpy().reshape(-1, d)
+    check_against_oracle(ifa, O, Qq, Kq, Vq, sQ, sK, sV, causal, label=f"extremes d={d} causal={causal}")
+    flat = O.reshape(heads, N, d)[:, 130:140]
+    if not causal:                                             # flat rows: O = s_V * column mean of V, exactly -128 / 127 s_V
+        assert np.allclose(flat[:, :, 3], -128.0 * sV[:, None], rtol=1e-6) and np.allclose(flat[:, :, 4], 127.0 * sV[:, None], rtol=1e-6)
+
+
 def test_degenerate_inputs(ifa):
     rng = np.random.default_rng(6)
     N, d = 256, 128
