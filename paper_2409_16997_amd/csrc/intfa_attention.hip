@@ -25,6 +25,11 @@
 // Softmax in base 2: log2(e) is folded into s_Q once per lane, the running max m2 is kept in log2
 // units and P = rint(exp2(acc * s_K * s_Q' - (m2 - log2 127))) with one v_exp_f32 per score and
 // v_cvt_pk_u8_f32 (round-half-even, measured) packing four P bytes per dword.
+//
+// The int32 results of both GEMMs are never converted: the accumulators start from a constant register block
+// holding the bit pattern of 1.5 * 2^23 (ACC_BIAS_I), so that a sum s reads as the float 1.5 * 2^23 + s, exactly,
+// and one fp32 subtraction recovers s.  The running output is kept negated so that its update is one three-address
+// fused multiply-add in place.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
