@@ -146,6 +146,15 @@ int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed char *K_i8, 
                               void *hip_stream);
 
 /*
+ * The same for N_q query rows against N_k keys: shapes and mask rule of int_flash_attn_fwd_rect, per-block V scales
+ * s_Vb [B, H, ceil(Nk / ifa_block_cols(d, causal))] of int_flash_attn_fwd_vblock (blocks count from key 0).
+ */
+int int_flash_attn_fwd_vblock_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                   const float *s_Q, const float *s_K, const float *s_Vb,
+                                   int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype,
+                                   void *hip_stream);
+
+/*
  * Half-INT8 variant (Section 4: "INT8-format Q and K matrices and FP16-format V matrix"): lines 9-10 of
  * Algorithm 1 as above, then the softmax weights stay real and are rounded to FP16 for the second GEMM:
  *   P~ = fp16(exp(S - m))  (nearest even, no factor R);   l = e^{m_old - m} l + rowsum(P~)  (the rounded weights, fp32)

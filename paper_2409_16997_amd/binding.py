@@ -23,6 +23,7 @@ SIGNATURES = {
     "int_flash_attn_fwd_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
     "quantize_blockwise": (_i, [_vp, _i, _l, _l, _i, _i, _vp, _vp, _vp]),
     "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
+    "int_flash_attn_fwd_vblock_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
     "ifa_block_cols": (_i, [_i, _i]),
     "int_flash_attn_fwd_half": (_i, [_vp] * 5 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_half_rect": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _i, _vp]),
@@ -140,15 +141,14 @@ def int_flash_attn_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=
     args = (_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
             _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32))
     tail = (d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
+    if K_i8.shape != (B, H, Nk, d) or V_i8.shape != K_i8.shape or s_K.shape != (B, H, Nk) or s_Q.shape != (B, H, N):
+        raise IntfaError("Q/K/V/scale shapes do not agree")
     if s_V.dim() == 3:
-        if Nk != N:
-            raise IntfaError("per-block s_V is built for Nq == Nk only")
-        if s_V.shape != (B, H, -(-N // block_cols(d, causal))):
+        if s_V.shape != (B, H, -(-Nk // block_cols(d, causal))):
             raise IntfaError(f"per-block s_V has shape {tuple(s_V.shape)}")
-        code = lib().int_flash_attn_fwd_vblock(*args, B, H, N, *tail)
+        code = (lib().int_flash_attn_fwd_vblock(*args, B, H, N, *tail) if Nk == N else
+                lib().int_flash_attn_fwd_vblock_rect(*args, B, H, N, Nk, *tail))
     elif Nk != N:
-        if K_i8.shape != (B, H, Nk, d) or V_i8.shape != K_i8.shape or s_K.shape != (B, H, Nk) or s_Q.shape != (B, H, N):
-            raise IntfaError("Q/K/V/scale shapes do not agree")
         code = lib().int_flash_attn_fwd_rect(*args, B, H, N, Nk, *tail)
     else:
         code = lib().int_flash_attn_fwd_ex(*args, B, H, N, *tail)

@@ -636,6 +636,12 @@ extern "C" int int_flash_attn_fwd_vblock(const signed char *Q_i8, const signed c
     return fwd_entry<true>(Q_i8, K_i8, V_i8, s_Q, s_K, s_Vb, B, H, N, N, d, causal, O, o_dtype, hip_stream);
 }
 
+extern "C" int int_flash_attn_fwd_vblock_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                              const float *s_Q, const float *s_K, const float *s_Vb, int B, int H, int Nq,
+                                              int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream) {
+    return fwd_entry<true>(Q_i8, K_i8, V_i8, s_Q, s_K, s_Vb, B, H, Nq, Nk, d, causal, O, o_dtype, hip_stream);
+}
+
 extern "C" int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                                        const float *s_Q, const float *s_K, const float *s_V, int B, int H, int Nq, int Nk,
                                        int d, int causal, void *O, int o_dtype, void *hip_stream) {

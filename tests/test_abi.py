@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -87,6 +87,8 @@ def test_argument_validation_happens_on_the_host(L):
     assert b(p, 7, 4, 256, 128, 128, p, p, None) == -3 and b(p, 1, 4, 256, 128, 256, p, p, None) == -4
     assert L.int_flash_attn_fwd_vblock(p, p, p, p, p, null, 1, 1, 128, 128, 0, p, 1, None) == -1
     assert L.int_flash_attn_fwd_vblock(p, p, p, p, p, p, 1, 1, 128, 96, 0, p, 1, None) == -4
+    vr = L.int_flash_attn_fwd_vblock_rect
+    assert vr(p, p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4 and vr(p, p, p, p, p, null, 1, 1, 8, 64, 128, 0, p, 1, None) == -1
     rc = L.int_flash_attn_fwd_rect
     assert rc(p, p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4             # causal with Nk < Nq
     assert rc(p, p, p, p, p, p, 1, 1, 0, 64, 128, 0, p, 1, None) == -2 and rc(p, p, p, p, p, null, 1, 1, 8, 64, 128, 0, p, 1, None) == -1

@@ -476,6 +476,24 @@ def test_attention_with_blockwise_v_scales(ifa, B, H, N, d, dist, causal):
     assert np.array_equal(gq.cpu().numpy().reshape(Vq.shape), Vq) and np.array_equal(gs.cpu().numpy().reshape(sVb.shape), sVb)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,d", [(1, 1000, 128), (128, 512, 128), (100, 333, 128), (256, 1024, 64), (130, 131, 128), (37, 700, 64)])
+def test_rectangular_problems_with_blockwise_v_scales(ifa, Nq, Nk, d, causal):
+    # N_q != N_k together with one V scale per key block: chunked prefill / decode against per-block-quantized V
+    B, H = 1, 3
+    w = workloads.custom("t", B, H, Nk, d, causal, dist="student_t3", seed=Nq + Nk + d)
+    x = quantized_inputs(w, scaled=True)
+    Bc = ifa.block_cols(d, causal)
+    Vq, sVb = oracle.quantize_blockwise(x["V"], Bc)
+    Qq, sQ = x["Qq"][:, Nk - Nq:], x["sQ"][:, Nk - Nq:]       # the last Nq positions as queries
+    O = ifa.int_flash_attn_fwd(dev(Qq.reshape(B, H, Nq, d)), dev(x["Kq"].reshape(B, H, Nk, d)), dev(Vq.reshape(B, H, Nk, d)),
+                               dev(sQ.reshape(B, H, Nq)), dev(x["sK"].reshape(B, H, Nk)), dev(sVb.reshape(B, H, -1)),
+                               causal=causal, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), Qq, x["Kq"], Vq, sQ, x["sK"], sVb, causal,
+                         label=f"block-V rect {Nq}x{Nk}x{d} causal={causal}")
+
+
 def test_blockwise_v_scales_improve_heavy_tailed_accuracy(ifa):
     # the reason for per-block scales: a few loud tokens no longer set the resolution of the whole head
     w = workloads.custom("t", 1, 4, 2048, 128, True, dist="student_t3", seed=99)

@@ -1,6 +1,7 @@
 """Pins for the oracle's attention functions against what the paper and the mathematics fix:
 Section 2.1 (standard attention), Section 3.1 (online softmax equals standard softmax),
 Algorithm 1 and Section 3.2 (INT8 P with S_P = 1/R cancelling in diag(l)^-1)."""
+import itertools
 import math
 
 import numpy as np
@@ -365,9 +366,10 @@ def test_rectangular_rows_are_rows_of_the_square_problem(Bc):
     rng = np.random.default_rng(31)
     N, Nq, d = 160, 48, 32
     Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, 2, N, d, score_sigma=2.0)
-    for causal in (False, True):
-        full = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc, want_P=True)
-        rect = oracle.int_flash_attn_fwd(Qq[:, N - Nq:], Kq, Vq, sQ[:, N - Nq:], sK, sV, causal, Bc, want_P=True)
+    sVb = rng.uniform(0.01, 0.2, (2, -(-N // Bc))).astype(np.float32)      # one V scale per key block
+    for causal, sv in itertools.product((False, True), (sV, sVb)):
+        full = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sv, causal, Bc, want_P=True)
+        rect = oracle.int_flash_attn_fwd(Qq[:, N - Nq:], Kq, Vq, sQ[:, N - Nq:], sK, sv, causal, Bc, want_P=True)
         pick = (np.arange(2)[:, None] * N + np.arange(N - Nq, N)[None, :]).ravel()
         for key in ("O", "l", "m", "P"):
             assert np.array_equal(rect[key], full[key][pick]), key
