@@ -47,9 +47,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=50,
                     help="untimed steps; the clocks need some tens of steps of load before the step time settles")
     ap.add_argument("--workload", default="c3", help="c1..c5 (default: the headline config, c3)")
-    ap.add_argument("--variant", default="full", choices=["full", "half"],
+    ap.add_argument("--variant", default="full", choices=["full", "half", "vblock"],
                     help="full: Algorithm 1 (INT8 P and V), the headline; half: the half-INT8 variant of Section 4 "
-                         "(INT8 Q, K; fp16 weights and V; V is passed as it is, only Q and K are quantized)")
+                         "(INT8 Q, K; fp16 weights and V; V is passed as it is, only Q and K are quantized); "
+                         "vblock: Algorithm 1 with one V scale per key block (the paper's stated next step)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -97,6 +98,7 @@ def main():
     state = {}
 
     half = args.variant == "half"
+    vblock = args.variant == "vblock"          # Algorithm 1 with one V scale per key block instead of one per head
     if half and w.in_dtype != "float16":
         sys.exit("bench.py: --variant half needs an fp16 workload (V is consumed as fp16)")
 
@@ -105,7 +107,10 @@ def main():
             Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
             Kq, sK = ifa.quantize_tokenwise(K)
             state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK)
-            if not half:
+            if vblock:
+                Vq, sV = ifa.quantize_blockwise(V, ifa.block_cols(w.d, w.causal))
+                state.update(Vq=Vq, sV=sV)
+            elif not half:
                 Vq, sV = ifa.quantize_headwise(V)
                 state.update(Vq=Vq, sV=sV)
         s = state
@@ -149,6 +154,8 @@ def main():
     quant_bytes = elems * (3 * in_bytes + in_bytes + 3) + 4 * (2 * w.heads * w.N + w.heads)
     if half:                                   # only Q and K are quantized
         quant_bytes = elems * (2 * in_bytes + 2) + 4 * 2 * w.heads * w.N
+    if vblock:                                 # V is read once: a block stays in registers between absmax and rounding
+        quant_bytes = elems * (3 * in_bytes + 3) + 4 * (2 * w.heads * w.N + w.heads * -(-w.N // ifa.block_cols(w.d, w.causal)))
     # roofline peak: both GEMMs on INT8 MFMA, or (half) one on INT8 and one on fp16 MFMA at half the rate
     peak = PEAK_INT8_TOPS if not half else 2.0 / (1.0 / PEAK_INT8_TOPS + 1.0 / PEAK_F16_TFLOPS)
     kernel_name = "int_flash_attn_fwd_half_kernel" if half else "int_flash_attn_fwd_kernel"
@@ -160,7 +167,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if w.causal else 'non-causal'} "
                                f"{w.dist} {w.in_dtype} in, {w.out_dtype} out; step = "
-                               + ("quantize Q,K + half-INT8 fused attention (fp16 V)" if half else "quantize Q,K,V + fused attention"),
+                               + ("quantize Q,K + half-INT8 fused attention (fp16 V)" if half else
+                                  "quantize Q,K,V (V per key block) + fused attention" if vblock else "quantize Q,K,V + fused attention"),
                    "variant": args.variant,
                    "block_cols": ifa.block_cols_half(w.d, w.causal) if half else ifa.block_cols(w.d, w.causal),
                    "softmax_scale": "1/sqrt(d) folded into s_Q",
@@ -168,7 +176,7 @@ def main():
         "pct_of_int8_mfma_peak": round(100 * tops_step / PEAK_INT8_TOPS, 2),
         "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": round(tops_attn, 2),
                      "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(tops_attn / peak, 4),
-                     "traffic": None if half else read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
+                     "traffic": None if (half or vblock) else read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
                      "min_launch_ms": round(attn_ms_min, 4),
                      "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s"
                              + ("; half variant: peak is the harmonic mix of the INT8 (first GEMM) and fp16 (second GEMM) "
@@ -193,7 +201,7 @@ def main():
             if half:
                 ref = oracle.int_flash_attn_fwd_half(Qq, Kq, v, sQ, sK, w.causal, ifa.block_cols_half(w.d, w.causal))
             else:
-                Vq, sV = oracle.quantize_headwise(v)
+                Vq, sV = oracle.quantize_blockwise(v, ifa.block_cols(w.d, w.causal)) if vblock else oracle.quantize_headwise(v)
                 ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal))
             t_cpu += time.perf_counter() - t2
             if h < 2:                         # the timed oracle output doubles as a parity check of this run
@@ -204,7 +212,7 @@ def main():
         result["cpu_baseline"] = {"value": round(cpu_ops / t_cpu / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
                                   "kind": "oracle", "seconds": round(t_cpu, 2),
                                   "sample": f"{n_heads} of {w.heads} heads of {w.name} (all rows), quantize + "
-                                            + ("half-INT8 variant" if half else "Algorithm 1")}
+                                            + ("half-INT8 variant" if half else "Algorithm 1, per-block V scales" if vblock else "Algorithm 1")}
         result["parity_max_rel_err_vs_oracle"] = worst   # out-dtype rounding included (fp16 output: <= 2^-11 of |O|)
 
         # ---- MRE against fp64 attention of the unquantized activations, beside fp16 and tensor-level FP8
@@ -215,7 +223,8 @@ def main():
         got = O[0, 0].float().cpu().numpy()[rows]
         result["mre_vs_fp64"] = {
             "rows": int(rows.size), "definition": "sum|dO|/sum|O| over sampled rows of head 0",
-            ("int8_half (this kernel)" if half else "int8_full (this kernel)"): baselines.mre(got, ref64)["sum_ratio"],
+            ("int8_half (this kernel)" if half else "int8_full, per-block V scales (this kernel)" if vblock
+             else "int8_full (this kernel)"): baselines.mre(got, ref64)["sum_ratio"],
             "fp16": baselines.mre(baselines.attention_fp16(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
             "fp8_e4m3_tensor_scale": baselines.mre(baselines.attention_fp8_tensor(q, k, v, rows, w.causal, fold), ref64)["sum_ratio"],
         }

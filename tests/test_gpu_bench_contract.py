@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("variant", ["full", "half"])
+@pytest.mark.parametrize("variant", ["full", "half", "vblock"])
 def test_bench_prints_one_json_line_with_the_contract_fields(variant):
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "c2", "--steps", "5", "--warmup", "2",
                         "--variant", variant], capture_output=True, text=True, timeout=500)
