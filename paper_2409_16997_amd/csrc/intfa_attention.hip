@@ -34,6 +34,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "intfa.h"
 #include "intfa_internal.h"
@@ -199,7 +200,8 @@ template <int D> struct RowState {
 // Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: a block with masked keys --
 // the block on the causal diagonal (query block == key block: keys beyond the query are masked) or the
 // ragged last block (keys at or beyond N are masked).  A key of the block is kept iff its index inside the
-// block is <= klimit (per lane); 32-key tiles after tile `last` (wave-uniform) are masked for every lane of
+// block is <= klimit (per lane); the first `clear_tiles` 32-key tiles (wave-uniform) hold no masked key for any
+// lane of the wavefront; 32-key tiles after tile `last` (wave-uniform) are masked for every lane of
 // the wavefront and are skipped (their P is 0).  `wave` is wave-uniform.
 //
 // The source is software-pipelined: LDS operands of the next MFMA group are requested before the
@@ -208,7 +210,7 @@ template <int D> struct RowState {
 // MFMA/VALU interleave with scheduling barriers measured no better than the compiler's own order.
 template <int D, bool DIAG, bool VB>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
-                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile,
+                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
                                               int g, float oscale, const Prefetch &nx, const v16i &bias, RowState<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
@@ -227,16 +229,21 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         for (int vq = 0; vq < 4; ++vq) skr[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
     };
     // line 9, fp32 part: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
-    auto scale_tile = [&](int mt, const v16i &s, const v4f (&skv)[4]) {
+    auto scale_elems = [&](int mt, const v16i &s, const v4f (&skv)[4], auto masked) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float x = (__int_as_float(s[4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
-                if (DIAG && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
+                if (decltype(masked)::value && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
+    };
+    // only the tiles the mask boundary crosses pay for the comparisons (wave-uniform choice)
+    auto scale_tile = [&](int mt, const v16i &s, const v4f (&skv)[4]) {
+        if (DIAG && mt >= clear_tiles) scale_elems(mt, s, skv, std::true_type{});
+        else scale_elems(mt, s, skv, std::false_type{});
     };
 
     // ---- S^T = K Q^T, tile by tile; tile mt-1 is scaled while tile mt is in the matrix pipe.  One register set
@@ -418,7 +425,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const bool more = jb + 1 < nblocks;
         const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
                              vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
-        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, g, oscale, pf, bias, st);
+        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, 4, g, oscale, pf, bias, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
@@ -432,12 +439,13 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const int tail = Nk - 1 - j0;
         const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;
         const int wlim = CAUSAL ? min(first_q + 32 * wave + 31 + shift - j0, tail) : tail;
+        const int wmin = CAUSAL ? min(first_q + 32 * wave + shift - j0, tail) : tail;   // klimit of the wavefront's first row
         if (wlim >= 0) {                                         // wave-uniform: this wavefront sees part of the block
             const Prefetch none = {rK, rV, rSK, NOWHERE, NOWHERE, kbuf, vbuf, skbuf};   // masked blocks request nothing
             const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
             const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
             sv_prev = sv_j;
-            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), g, oscale, none, bias, st);
+            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, bias, st);
         }
     };
     if (nfull < nblocks) {

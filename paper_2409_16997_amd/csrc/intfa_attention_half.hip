@@ -19,6 +19,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "intfa.h"
 #include "intfa_internal.h"
@@ -109,10 +110,11 @@ template <int D> struct RowStateH {
 
 // One key block already resident in LDS.  MASKED: a block with masked keys (on or past the causal diagonal, or the
 // ragged last block): a key of the block is kept iff its index inside the block is <= klimit (per lane, may be
-// negative); 32-key tiles after tile `last` (wave-uniform, -1: none) are masked for every lane and skipped.
+// negative); the first `clear_tiles` 32-key tiles (wave-uniform) hold no masked key for any lane of the wavefront;
+// 32-key tiles after tile `last` (wave-uniform, -1: none) are masked for every lane and skipped.
 template <int D, bool MASKED>
 __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsetsH<D> &lo,
-                                                   const v4i (&qf)[D / 32], float sq2, int klimit, int last_tile, int g,
+                                                   const v4i (&qf)[D / 32], float sq2, int klimit, int last_tile, int clear_tiles, int g,
                                                    const v16i &bias, RowStateH<D> &st) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = MASKED ? last_tile : NT - 1;
@@ -131,16 +133,21 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) skr[buf][vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + 16 * g + 128 * mt + 32 * vq);
     };
-    auto scale_tile = [&](int mt, const v16i &acc, const v4f (&skv)[4]) {       // line 9, fp32 part: a = acc * s_K
+    auto scale_elems = [&](int mt, const v16i &acc, const v4f (&skv)[4], auto masked) {   // line 9, fp32 part: a = acc * s_K
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float x = (__int_as_float(acc[4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
-                if (MASKED && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
+                if (decltype(masked)::value && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
+    };
+    // only the tiles the mask boundary crosses pay for the comparisons (wave-uniform choice)
+    auto scale_tile = [&](int mt, const v16i &acc, const v4f (&skv)[4]) {
+        if (MASKED && mt >= clear_tiles) scale_elems(mt, acc, skv, std::true_type{});
+        else scale_elems(mt, acc, skv, std::false_type{});
     };
     // V^T operands of d tile dt: one h8 per 16-key step of the active tiles
     h8 vop[2][2 * NT];
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
         const int cur = jb & 1;
         prefetch_block<D>(next_block(jb), lo, wave, lane);
         process_block_half<D, false>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
-                                     0, NT - 1, g, bias, st);
+                                     0, NT - 1, NT, g, bias, st);
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and `cur` is free again
     }
@@ -318,9 +325,10 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
         const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;         // < 0: nothing kept
         const int wlim = CAUSAL ? min(wave_last_q + shift - j0, tail) : tail;
         const int last_tile = wlim < 0 ? -1 : min(NT - 1, wlim >> 5);
+        const int wmin = CAUSAL ? min(wave_last_q - 31 + shift - j0, tail) : tail;   // klimit of the wavefront's first row
         if (last_tile >= 0)                                                        // wave-uniform
             process_block_half<D, true>(kbuf + cur * BCH * D, vbuf + cur * BCH * D * 2, skbuf + cur * BCH * 4, lo, qf, sq2,
-                                        klimit, last_tile, g, bias, st);
+                                        klimit, last_tile, max(0, (wmin + 1) >> 5), g, bias, st);
         wait_all_memory();
         __syncthreads();
     }
