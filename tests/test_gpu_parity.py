@@ -386,6 +386,18 @@ def test_accumulator_extremes_through_the_fused_kernel(ifa, d, causal):
         assert np.allclose(flat[:, :, 3], -128.0 * sV[:, None], rtol=1e-6) and np.allclose(flat[:, :, 4], 127.0 * sV[:, None], rtol=1e-6)
 
 
+@pytest.mark.parametrize("H,N,d,causal", [(2, 100003, 128, True), (4, 70001, 64, False)])
+def test_very_long_ragged_sequences_sampled_rows(ifa, H, N, d, causal):
+    # hundreds of key blocks per workgroup, N odd: first, last and seeded rows of every head against the oracle
+    w = workloads.custom("t", 1, H, N, d, causal, dist="normal", seed=N % 1000)
+    x = quantized_inputs(w, scaled=True)
+    rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(N - 130, N), np.random.default_rng(1).integers(0, N, 150)]))
+    idx = np.concatenate([h * N + rows for h in range(H)]).astype(np.int64)
+    O = run_gpu(ifa, x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], 1, H, causal).cpu().numpy().reshape(-1, d)
+    check_against_oracle(ifa, O[idx], x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], causal, row_idx=idx,
+                         label=f"long N={N} d={d} causal={causal}")
+
+
 def test_degenerate_inputs(ifa):
     rng = np.random.default_rng(6)
     N, d = 256, 128
