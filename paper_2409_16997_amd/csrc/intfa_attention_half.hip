@@ -352,7 +352,7 @@ int launch_half(const int8_t *Q, const int8_t *K, const _Float16 *V, const float
                 void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_half_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, heads, Nq, Nk, HEAD_GROUP, static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, heads, Nq, Nk, head_group_for(CAUSAL, 3L * Nk * D), static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 

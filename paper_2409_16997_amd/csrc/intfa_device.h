@@ -28,9 +28,17 @@ constexpr float LOG2E = 1.44269504088896340736f;
 constexpr int ACC_BIAS_I = 0x4B400000;
 constexpr float ACC_BIAS_F = 12582912.0f;
 
-// Heads an XCD works on at a time: 4 heads of K and V (N = 4096, d = 128: 4 MB) fit its 4 MB L2, and a group
-// of 4 gave the shortest causal run of the group sizes 1, 2, 4, 8, 16 measured on MI355X.
+// Heads an XCD works on at a time.  Under the mask a group of 4 gave the shortest run of the group sizes 1 .. 16
+// at every length measured on MI355X (larger groups balance the uneven query blocks better, smaller ones keep less
+// K and V live).  Without the mask every workgroup of a head walks all of its K and V, and what the group streams
+// at a time should fit the XCD's 4 MB L2: 4 MB / (K + V bytes of a head), between 1 and 4 (measured: long unmasked
+// sequences run 1.5-2.5 % faster with 1 or 2 heads than with 4).
 constexpr int HEAD_GROUP = 4;
+inline int head_group_for(bool causal, long kv_bytes_per_head) {
+    if (causal) return HEAD_GROUP;
+    const long fit = (4L << 20) / (kv_bytes_per_head > 0 ? kv_bytes_per_head : 1);
+    return static_cast<int>(fit < 1 ? 1 : (fit > HEAD_GROUP ? HEAD_GROUP : fit));
+}
 
 // Workgroups go round-robin over the 8 XCDs by linear id.  All query blocks of a head run on one XCD,
 // so its K/V stay in that XCD's L2; an XCD takes its heads `head_group` at a time and, inside a group,
