@@ -561,7 +561,7 @@ int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *s
                int heads, int Nq, int Nk, void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, VB, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, sV, heads, Nq, Nk, head_group_for(CAUSAL, 2L * Nk * D), static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, sV, heads, Nq, Nk, head_group_for(CAUSAL, 2L * Nk * D, (Nq + BR - 1) / BR), static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 

@@ -351,8 +351,9 @@ template <int D, bool CAUSAL, typename OutT>
 int launch_half(const int8_t *Q, const int8_t *K, const _Float16 *V, const float *sQ, const float *sK, int heads, int Nq, int Nk,
                 void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
+    // T_r = 0: under the mask this kernel keeps 4 heads per group (8 measured 4-17 % slower here at N = 1280 .. 2048)
     hipLaunchKernelGGL((int_flash_attn_fwd_half_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, heads, Nq, Nk, head_group_for(CAUSAL, 3L * Nk * D), static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, heads, Nq, Nk, head_group_for(CAUSAL, 3L * Nk * D, 0), static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 

@@ -28,15 +28,16 @@ constexpr float LOG2E = 1.44269504088896340736f;
 constexpr int ACC_BIAS_I = 0x4B400000;
 constexpr float ACC_BIAS_F = 12582912.0f;
 
-// Heads an XCD works on at a time.  Under the mask a group of 4 gave the shortest run of the group sizes 1 .. 16
-// at every length measured on MI355X (larger groups balance the uneven query blocks better, smaller ones keep less
-// K and V live).  Without the mask every workgroup of a head walks all of its K and V, and what the group streams
-// at a time should fit the XCD's 4 MB L2: 4 MB / (K + V bytes of a head), between 1 and 4 (measured: long unmasked
-// sequences run 1.5-2.5 % faster with 1 or 2 heads than with 4).
+// Heads an XCD works on at a time (measured on MI355X over group sizes 1 .. 32; the default 4 is never far off).
+// Without the mask every workgroup of a head walks all of its K and V, and what a group streams at a time should fit
+// the XCD's 4 MB L2: 4 MB / (K + V bytes of a head), between 1 and 4 (long sequences run 2-3 % faster with 1 or 2
+// heads than with 4).  Under the mask the query blocks of a head are uneven and run heaviest first, and more heads
+// per group even the 64 workgroup slots of an XCD out better: 8 heads when their K and V still fit the L2 and a head
+// has at least 10 query blocks (N = 2048, d = 128: +5 % over 4; no gain below, a loss once 8 heads exceed the L2).
 constexpr int HEAD_GROUP = 4;
-inline int head_group_for(bool causal, long kv_bytes_per_head) {
-    if (causal) return HEAD_GROUP;
+inline int head_group_for(bool causal, long kv_bytes_per_head, int T_r) {
     const long fit = (4L << 20) / (kv_bytes_per_head > 0 ? kv_bytes_per_head : 1);
+    if (causal) return (fit >= 8 && T_r >= 10) ? 8 : HEAD_GROUP;
     return static_cast<int>(fit < 1 ? 1 : (fit > HEAD_GROUP ? HEAD_GROUP : fit));
 }
 
