@@ -163,6 +163,25 @@ def test_degenerate_inputs(ifa):
     check(ifa, O.reshape(-1, d), x, False, d, label="dominant key")
 
 
+@pytest.mark.parametrize("dtype", ["float16", "bfloat16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(1, 128), (33, 64), (127, 128), (129, 64), (200, 128), (515, 128)])
+def test_ragged_lengths_with_two_byte_outputs(ifa, N, d, causal, dtype):
+    # 2-byte outputs leave through the staged row-wise store: rows past N must not be written (canaries on both
+    # sides of O) and the values must be the fp32 result rounded once
+    heads = 3
+    w = workloads.custom("t", 1, heads, N, d, causal, dist="normal", seed=19 * N + d)
+    x = inputs(w)
+    tdt = getattr(torch, dtype)
+    guard = 256
+    Obuf = torch.full((guard + heads * N + guard, d), 77.0, dtype=tdt, device="cuda")
+    O = Obuf[guard:guard + heads * N].view(1, heads, N, d)
+    run(ifa, x, 1, heads, N, d, causal, out=O)
+    O32 = run(ifa, x, 1, heads, N, d, causal, torch.float32)
+    assert bool((Obuf[:guard] == 77.0).all()) and bool((Obuf[guard + heads * N:] == 77.0).all())
+    assert torch.equal(O, O32.to(tdt))
+
+
 def test_output_dtypes_and_determinism(ifa):
     B, H, N, d = 1, 4, 384, 128
     w = workloads.custom("t", B, H, N, d, True, dist="normal", seed=11)
