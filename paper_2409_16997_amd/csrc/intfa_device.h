@@ -113,14 +113,13 @@ __device__ __forceinline__ float swap32(float x) {   // value held by lane ^ 32
 }
 
 // ---- output conversion --------------------------------------------------------------------------
-// O is written once and never read back by these kernels: the 16-byte stores carry the non-temporal hint so that the
-// output does not displace K and V in the L2 (measured +1.5 % on the headline workload; 8-byte pieces must not carry
-// it: they measured 3-6 % slower with it than without).
+// O is written once and never read back by these kernels.  The whole-row stores of store_tile_staged carry the
+// non-temporal hint, so that the output does not displace K and V in the L2 (+1.5 % on the headline workload); the
+// per-lane 8- and 16-byte pieces below must not: with the hint they measured 2-6 % slower than without.
 template <typename T> struct Store4;
 template <> struct Store4<float> {
     static __device__ __forceinline__ void put(float *p, float a, float b, float c, float d) {
-        const v4f x = {a, b, c, d};
-        __builtin_nontemporal_store(x, reinterpret_cast<v4f *>(p));
+        *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
     }
 };
 template <> struct Store4<__half> {
