@@ -229,6 +229,23 @@ def test_head_counts_and_grid_shapes(ifa, B, H):
                          label=f"heads {B}x{H}")
 
 
+@pytest.mark.parametrize("B,H,N,d,causal", [(3, 40, 1500, 128, True),      # masked, 12 query blocks: 8 heads per XCD group, last group short
+                                             (2, 32, 2048, 64, True),       # 8 heads per group, d = 64
+                                             (1, 24, 16384, 128, False),    # unmasked, 4 MB of K + V per head: 1 head per group
+                                             (1, 24, 8192, 128, False)])    # 2 heads per group, 3 heads per XCD
+def test_head_group_sizes_sampled_rows(ifa, B, H, N, d, causal):
+    # every size of the per-XCD head group the launcher picks; every head must come out, each exactly once:
+    # first, last and seeded rows of every head against the oracle
+    w = workloads.custom("t", B, H, N, d, causal, dist="normal", seed=N + H)
+    x = quantized_inputs(w, scaled=True)
+    heads = B * H
+    rows = np.unique(np.concatenate([np.arange(0, 3), np.arange(N - 3, N), np.random.default_rng(H).integers(0, N, 10)]))
+    idx = np.concatenate([h * N + rows for h in range(heads)]).astype(np.int64)
+    O = run_gpu(ifa, x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], B, H, causal).cpu().numpy().reshape(-1, d)
+    check_against_oracle(ifa, O[idx], x["Qq"], x["Kq"], x["Vq"], x["sQ"], x["sK"], x["sV"], causal, row_idx=idx,
+                         label=f"head groups {B}x{H}x{N}x{d} causal={causal}")
+
+
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("N,d", [(1, 128), (37, 64), (127, 128), (129, 128), (200, 64), (333, 128), (1000, 128), (515, 64)])
 def test_ragged_sequence_lengths(ifa, N, d, causal):
