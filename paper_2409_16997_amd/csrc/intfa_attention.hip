@@ -361,7 +361,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;                           // this lane's query inside the block
     const int q_head = qb * BR + q_local;                        // this lane's query inside the head
-    const bool q_valid = q_head < Nq;                            // rows past Nq are computed on a clamped copy, never stored
+    // rows past Nq are computed on a clamped copy of the last row and never stored
     const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);
 
     const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
@@ -468,24 +468,13 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
     const float l = st.l + swap32(st.l);
     const float f = -(VB ? sv_prev : sVh[0]) / l;                // st.o holds -O (in units of the last block's scale if VB)
-    if constexpr (sizeof(OutT) == 2) {
-        // The buffers the last block did not use are free for every wavefront since the barrier before it.
-        const int freeb = nblocks & 1;
-        const lds_ptr stage = (wave < 2 ? kbuf : vbuf) + freeb * BC * D + (wave & 1) * (64 * D);
-        const int row0 = qb * BR + 32 * wave;                    // first query row of this wavefront
-        OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
-        store_tile_staged<D, OutT>(stage, orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
-    } else {
-        OutT *orow = O + qrow * D;
-        if (q_valid) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq)
-                    Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
-                                      st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
-        }
-    }
+    // The buffers the last block did not use are free for every wavefront since the barrier before it: each
+    // wavefront stages its tile in its own 64 D bytes of them and stores whole (fp32: half) rows.
+    const int freeb = nblocks & 1;
+    const lds_ptr stage = (wave < 2 ? kbuf : vbuf) + freeb * BC * D + (wave & 1) * (64 * D);
+    const int row0 = qb * BR + 32 * wave;                        // first query row of this wavefront
+    OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
+    store_tile_staged<D, OutT>(stage, orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
 #endif
 }
 

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
     const int qb = CAUSAL ? (T_r - 1 - qord) : qord;
     const int q_local = 32 * wave + r;
     const int q_head = qb * BR + q_local;
-    const bool q_valid = q_head < Nq;                            // rows past Nq are computed on a clamped copy, never stored
+    // rows past Nq are computed on a clamped copy of the last row and never stored
     const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);
 
     const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
@@ -335,23 +335,11 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_half_kernel(
 
     const float l = st.l + swap32(st.l);
     const float f = 1.0f / l;
-    if constexpr (sizeof(OutT) == 2) {
-        // Every block ends with a barrier, so all of LDS is free here: each wavefront stages its 32 x D tile in its own
-        // 64 D bytes of the V buffers and stores whole rows.
-        const int row0 = qb * BR + 32 * wave;                    // first query row of this wavefront
-        OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
-        store_tile_staged<D, OutT>(vbuf + wave * (64 * D), orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
-    } else {
-        OutT *orow = O + qrow * D;
-        if (q_valid) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq)
-                    Store4<OutT>::put(orow + 32 * dt + 8 * vq + 4 * g, st.o[dt][4 * vq] * f, st.o[dt][4 * vq + 1] * f,
-                                      st.o[dt][4 * vq + 2] * f, st.o[dt][4 * vq + 3] * f);
-        }
-    }
+    // Every block ends with a barrier, so all of LDS is free here: each wavefront stages its 32 x D tile in its own
+    // 64 D bytes of the V buffers and stores whole (fp32: half) rows.
+    const int row0 = qb * BR + 32 * wave;                        // first query row of this wavefront
+    OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
+    store_tile_staged<D, OutT>(vbuf + wave * (64 * D), orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
 #endif
 }
 

@@ -113,16 +113,12 @@ __device__ __forceinline__ float swap32(float x) {   // value held by lane ^ 32
 }
 
 // ---- output conversion --------------------------------------------------------------------------
-// O is written once and never read back by these kernels.  The whole-row stores of store_tile_staged carry the
-// non-temporal hint, so that the output does not displace K and V in the L2 (+1.5 % on the headline workload); the
-// per-lane 8- and 16-byte pieces below must not: with the hint they measured 2-6 % slower than without.
-template <typename T> struct Store4;
-template <> struct Store4<float> {
-    static __device__ __forceinline__ void put(float *p, float a, float b, float c, float d) {
-        *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
-    }
-};
-template <> struct Store4<__half> {
+// O is written once and never read back by these kernels: the whole-row stores of store_tile_staged carry the
+// non-temporal hint, so that the output does not displace K and V in the L2 (+1.5 % on the headline workload).
+// (Per-lane 8- and 16-byte pieces stored straight from the accumulator layout measured 2-6 % slower with the hint
+// than without, and slower than the staged rows either way.)
+template <typename T> struct Pack4;                 // four fp32 values -> four 2-byte outputs, round half to even
+template <> struct Pack4<__half> {
     static __device__ __forceinline__ uint2 pack(float a, float b, float c, float d) {
         __half2 lo = __floats2half2_rn(a, b), hi = __floats2half2_rn(c, d);
         uint2 w;
@@ -130,11 +126,8 @@ template <> struct Store4<__half> {
         w.y = *reinterpret_cast<uint32_t *>(&hi);
         return w;
     }
-    static __device__ __forceinline__ void put(__half *p, float a, float b, float c, float d) {
-        *reinterpret_cast<uint2 *>(p) = pack(a, b, c, d);
-    }
 };
-template <> struct Store4<__hip_bfloat16> {
+template <> struct Pack4<__hip_bfloat16> {
     static __device__ __forceinline__ uint32_t rne(float x) {   // fp32 -> bf16 bits, round half to even
         uint32_t u = __float_as_uint(x);
         return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
@@ -145,39 +138,49 @@ template <> struct Store4<__hip_bfloat16> {
         w.y = rne(c) | (rne(d) << 16);
         return w;
     }
-    static __device__ __forceinline__ void put(__hip_bfloat16 *p, float a, float b, float c, float d) {
-        *reinterpret_cast<uint2 *>(p) = pack(a, b, c, d);
-    }
 };
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Writes a wavefront's 32 x D output tile (2-byte elements) through a private LDS region of 64 D bytes so that the
-// global stores are whole rows: in the accumulator layout a lane holds 4 consecutive d of one row per register
-// group, and storing those directly costs one 8-byte piece per row and instruction.  Staged, lane t stores 16
-// contiguous bytes and 16 (D = 128) or 8 (D = 64) lanes cover a row.  The 16-byte chunks of a row are XOR-swizzled
-// by the row so that the column-wise writes spread over the banks.  Only this wavefront touches `stage`; LDS
-// operations of one wavefront complete in order, so no barrier is needed between the two halves.
+// Writes a wavefront's 32 x D output tile through a private LDS region of 64 D bytes so that the global stores are
+// whole rows (2-byte outputs) or half rows (4-byte outputs, two passes over the region): in the accumulator layout a
+// lane holds 4 consecutive d of one row per register group, and storing those directly costs one 8- or 16-byte
+// piece per row and instruction.  Staged, lane t stores 16 contiguous bytes and 16 (D = 128) or 8 (D = 64) lanes
+// cover a row piece of 2 D bytes.  The 16-byte chunks of a row are XOR-swizzled by the row so that the column-wise
+// writes spread over the banks.  Only this wavefront touches `stage`; LDS operations of one wavefront complete in
+// order, so no barrier is needed between the writes and the reads, or between the passes.
 //   val(dt, v): element d = 32*dt + 8*(v/4) + 4*g + v%4 of row r = lane % 32 (g = lane / 32), already scaled
 //   rows_valid: rows at or beyond it are not stored;  orow0: address of row 0 of the tile, row stride D elements
 template <int D, typename OutT, typename F>
 __device__ __forceinline__ void store_tile_staged(lds_ptr stage, OutT *orow0, int rows_valid, int lane, F val) {
-    static_assert(sizeof(OutT) == 2, "staged store is for 2-byte outputs");
-    constexpr int CH = D * 2 / 16;                 // 16-byte chunks per row
+    static_assert(sizeof(OutT) == 2 || sizeof(OutT) == 4, "2- or 4-byte outputs");
+    constexpr int PASSES = sizeof(OutT) / 2;       // D/PASSES elements of every row per pass = 2 D bytes
+    constexpr int DTP = (D / 32) / PASSES;         // 32-wide d tiles per pass
+    constexpr int CH = D * 2 / 16;                 // 16-byte chunks per staged row piece
+    constexpr int ROWS_PER_READ = 64 / CH;
     const int r = lane & 31, g = lane >> 5;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            const uint2 w = Store4<OutT>::pack(val(dt, 4 * vq), val(dt, 4 * vq + 1), val(dt, 4 * vq + 2), val(dt, 4 * vq + 3));
-            *reinterpret_cast<LDS_AS uint2 *>(stage + r * (2 * D) + (((4 * dt + vq) ^ (r & (CH - 1))) * 16) + 8 * g) = w;
-        }
-    constexpr int ROWS_PER_PASS = 64 / CH;
     const int c = lane % CH, rr = lane / CH;
 #pragma unroll
-    for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
-        const int row = pass * ROWS_PER_PASS + rr;
-        const v4i x = *reinterpret_cast<LDS_AS const v4i *>(stage + row * (2 * D) + ((c ^ (row & (CH - 1))) * 16));
-        if (row < rows_valid) __builtin_nontemporal_store(x, reinterpret_cast<v4i *>(orow0 + static_cast<long>(row) * D + 8 * c));
+    for (int pass = 0; pass < PASSES; ++pass) {
+#pragma unroll
+        for (int dl = 0; dl < DTP; ++dl)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int dt = pass * DTP + dl;
+                if constexpr (sizeof(OutT) == 2) {
+                    const uint2 w = Pack4<OutT>::pack(val(dt, 4 * vq), val(dt, 4 * vq + 1), val(dt, 4 * vq + 2), val(dt, 4 * vq + 3));
+                    *reinterpret_cast<LDS_AS uint2 *>(stage + r * (2 * D) + (((4 * dl + vq) ^ (r & (CH - 1))) * 16) + 8 * g) = w;
+                } else {
+                    const v4f w = {val(dt, 4 * vq), val(dt, 4 * vq + 1), val(dt, 4 * vq + 2), val(dt, 4 * vq + 3)};
+                    *reinterpret_cast<LDS_AS v4f *>(stage + r * (2 * D) + (((8 * dl + 2 * vq + g) ^ (r & (CH - 1))) * 16)) = w;
+                }
+            }
+#pragma unroll
+        for (int rd = 0; rd < 32 / ROWS_PER_READ; ++rd) {
+            const int row = rd * ROWS_PER_READ + rr;
+            const v4i x = *reinterpret_cast<LDS_AS const v4i *>(stage + row * (2 * D) + ((c ^ (row & (CH - 1))) * 16));
+            char *dst = reinterpret_cast<char *>(orow0 + static_cast<long>(row) * D) + pass * (2 * D) + 16 * c;
+            if (row < rows_valid) __builtin_nontemporal_store(x, reinterpret_cast<v4i *>(dst));
+        }
     }
 }
 #endif
