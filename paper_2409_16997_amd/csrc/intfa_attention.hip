@@ -52,6 +52,8 @@ template <int D> struct Smem {
     alignas(1024) int8_t v[2][BC * D];   // V_j, row = key, 16-byte slots XOR-swizzled by row
     alignas(512) float sk[2][BC];        // s_K of the block
 };
+// lds_xor() wants every K / V tile at a multiple of 4096 bytes
+static_assert((BC * 64) % 4096 == 0 && offsetof(Smem<64>, v) % 4096 == 0 && offsetof(Smem<128>, v) % 4096 == 0, "tile bases");
 
 // Slot swizzles.  Logical 16-byte chunk c of row `row` is stored in slot c ^ swz(row).
 // K is read with ds_read_b128 by 32 consecutive rows at one chunk: 8 consecutive rows must fall in 8

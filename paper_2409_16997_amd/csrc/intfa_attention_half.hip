@@ -43,6 +43,8 @@ template <int D> struct SmemH {
     alignas(1024) int8_t v[2][BCH * D * 2];    // V_j fp16, row = key (2 D bytes), 64-byte chunks XOR-swizzled by row
     alignas(256) float sk[2][BCH];             // s_K of the block
 };
+// lds_xor() wants every K / V tile at a multiple of 4096 bytes
+static_assert((BCH * 64) % 4096 == 0 && offsetof(SmemH<64>, v) % 4096 == 0 && offsetof(SmemH<128>, v) % 4096 == 0, "tile bases");
 
 template <int D> __device__ __forceinline__ int kh_swz(int row) {
     return (D == 128) ? (row & 7) : ((row >> 1) & 3);
