@@ -32,5 +32,26 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+MICROBENCH_SRC = os.path.join(CSRC, "microbench", "issue_model.hip")
+MICROBENCH_BIN = os.path.join(_HERE, "issue_model_microbench.bin")
+
+
+def build_microbench(verbose: bool = False) -> str:
+    """The stand-alone issue-model micro-benchmark (register-only probes of the MFMA / vector ALU / exp pipes)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", MICROBENCH_SRC, "-o", MICROBENCH_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(ln for ln in res.stdout.splitlines() if "packed-fp32-ops" not in ln)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    return MICROBENCH_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_microbench(verbose=True))
