@@ -178,7 +178,9 @@ def main():
                      "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(tops_attn / peak, 4),
                      "traffic": None if (half or vblock) else read_traffic(w.name), "avg_launch_ms": round(attn_ms, 4),
                      "min_launch_ms": round(attn_ms_min, 4),
-                     "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s"
+                     "note": "unit counts integer operations (2 per int8 multiply-accumulate), i.e. TOP/s; traffic is not measured "
+                             "in this run: it is read from the committed rocprofv3 --pmc summary of this kernel and workload "
+                             "under profiles/ (FETCH_SIZE + WRITE_SIZE, calibrated on a plain copy)"
                              + ("; half variant: peak is the harmonic mix of the INT8 (first GEMM) and fp16 (second GEMM) "
                                 "MFMA peaks" if half else "")},
         "quantize_pass": {"ms": round(quant_ms, 4), "algorithmic_GBps": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
@@ -192,6 +194,8 @@ def main():
         n_heads = {"c1": 1, "c2": 64, "c3": 128, "c4": 24, "c5": 12}[w.name]   # about 4-6 s of oracle time on 16 cores
         t_cpu = 0.0
         worst = 0.0
+        tie_rows = 0
+        bar = 1e-3 + (2.0 ** -10 if w.out_dtype == "float16" else 0.0)   # the parity bar plus the output cast
         for h in range(n_heads):
             q, k, v = (workloads.head_tensor(w, t, h)[None] for t in "QKV")
             t2 = time.perf_counter()
@@ -204,16 +208,25 @@ def main():
                 Vq, sV = oracle.quantize_blockwise(v, ifa.block_cols(w.d, w.causal)) if vblock else oracle.quantize_headwise(v)
                 ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal))
             t_cpu += time.perf_counter() - t2
-            if h < 2:                         # the timed oracle output doubles as a parity check of this run
-                b, hh = divmod(h, w.H)
-                got = O[b, hh].float().cpu().numpy()
-                worst = max(worst, float(np.abs(got - ref["O"]).max() / np.abs(ref["O"]).max()))
+            b, hh = divmod(h, w.H)            # the timed oracle output doubles as a parity check of this run, every head
+            got = O[b, hh].float().cpu().numpy()
+            scale_h = float(np.abs(ref["O"]).max())
+            err_rows = np.abs(got - ref["O"]).max(axis=1)
+            bad = np.nonzero(err_rows > bar * scale_h)[0]
+            if bad.size and not half:         # (untimed) rows off the default resolution of line 11's near-tie roundings:
+                res = oracle.compare_up_to_ties(got[bad], Qq, Kq, Vq, sQ, sK, sV, w.causal, ifa.block_cols(w.d, w.causal),
+                                                row_idx=bad.astype(np.int64), tol=bar * scale_h / max(float(np.abs(ref["O"][bad]).max()), 1e-30))
+                err_rows[bad] = res["err"]    # ... must match the oracle with flagged entries rounded the other way
+                tie_rows += int((res["flips"] > 0).sum())
+            worst = max(worst, float(err_rows.max() / scale_h))
         cpu_ops = ops * n_heads / w.heads
         result["cpu_baseline"] = {"value": round(cpu_ops / t_cpu / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
                                   "kind": "oracle", "seconds": round(t_cpu, 2),
                                   "sample": f"{n_heads} of {w.heads} heads of {w.name} (all rows), quantize + "
                                             + ("half-INT8 variant" if half else "Algorithm 1, per-block V scales" if vblock else "Algorithm 1")}
         result["parity_max_rel_err_vs_oracle"] = worst   # out-dtype rounding included (fp16 output: <= 2^-11 of |O|)
+        result["parity_heads_compared"] = n_heads
+        result["parity_rows_matched_with_near_ties_rounded_the_other_way"] = tie_rows
 
         # ---- MRE against fp64 attention of the unquantized activations, beside fp16 and tensor-level FP8
         h = 0

@@ -181,14 +181,23 @@ int ifa_block_cols_half(int d, int causal);
 int ifa_block_cols(int d, int causal);
 
 /*
- * Test hooks: the exact int32 accumulators of the two GEMMs of Algorithm 1 (lines 9 and 13),
- * produced by the same device tile code the fused kernel runs.  One head, N a multiple of 128.
- *   ifa_debug_qk_i32:  S_i32 [N, N]  = Q_i8 [N, d] . K_i8 [N, d]^T
- *   ifa_debug_pv_i32:  PV_i32 [N, d] = P_i8 [N, N] . V_i8 [N, d],  P in [0, 127]
- * Both run on the ifa_set_stream() stream.
+ * Test hook: Algorithm 1 on ONE head through the production kernel, with its integer stages written out.  The kernel
+ * run here is the one int_flash_attn_fwd_ex launches, instantiated with stores below its accumulators; nothing else
+ * differs (same MFMA loops, same biased accumulators, same staging).  N must be a multiple of 128, at most 8192.
+ *   P_in    [N, N] int8 or null.  Non-null: these values replace the computed P of line 11 as the operand of the
+ *           second GEMM (and in the row sum l), which lets a test drive line 13 to the ends of its range.
+ *   S_i32   [N, N] int32 out or null: Q_i8 K_i8^T, the accumulator of line 9 (exact).  Under the causal mask, key
+ *           tiles of 32 that lie wholly above the diagonal for a whole wavefront are not computed and not written.
+ *   P_i8    [N, N] int8 out or null: P of line 11 as it enters the second GEMM (masked keys: 0; skipped tiles are
+ *           not written).
+ *   PV_i32  [N / B_c, N, d] int32 out or null: P_j V_j of line 13 for every key block j (exact); blocks a query
+ *           block does not visit under the mask are not written.
+ *   O       [N, d] fp32 out: the attention output, as from int_flash_attn_fwd_ex.
+ * Same argument rules and error codes as int_flash_attn_fwd_ex.
  */
-int ifa_debug_qk_i32(const signed char *Q_i8, const signed char *K_i8, int N, int d, int *S_i32);
-int ifa_debug_pv_i32(const signed char *P_i8, const signed char *V_i8, int N, int d, int *PV_i32);
+int ifa_debug_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                  const float *s_Q, const float *s_K, const float *s_V, int N, int d, int causal,
+                  const signed char *P_in, int *S_i32, signed char *P_i8, int *PV_i32, float *O, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -42,7 +42,7 @@ def _load():
         lib.orc_qk_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_pv_i32.argtypes = [vp, vp, i64, i32, vp]
         lib.orc_int_flash_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i64, i64, i32, i32, i32,
-                                               i32, i32, vp, i64, vp, vp, vp, f64, f64, vp, vp]
+                                               i32, i32, vp, i64, vp, vp, vp, f64, f64, vp, vp, vp]
         lib.orc_attention_fp64.argtypes = [vp, vp, vp, i64, i64, i32, i32, f64, vp, i64, vp]
         lib.orc_round_to_half.argtypes = [ctypes.c_float]
         lib.orc_round_to_half.restype = ctypes.c_float
@@ -151,11 +151,12 @@ def pv_i32(P, V):
 
 
 def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=None,
-                       tie_rel=0.0, tie_abs=0.0, want_P=False):
+                       tie_rel=0.0, tie_abs=0.0, want_P=False, tie_flip=None):
     """Algorithm 1.  Q int8 [heads, Nq, d], sQ fp32 [heads, Nq]; K, V int8 [heads, N, d], sK fp32 [heads, N]
     (Nq = N in the paper; with Nq != N the queries are the last Nq positions for the causal mask);
     sV fp32 [heads] (tensor-level scale of V) or [heads, ceil(N/Bc)] (one scale per key block, applied where
     P V_j enters O).
+    tie_flip: optional uint64 [rows]; bit k rounds the k-th flagged near-tie entry of that row the other way.
     Returns a dict: O fp32 [rows, d], l, m fp32 [rows], n_tie int32 [rows], P int8 [rows, N] (if asked)."""
     Q, K, V = _c(Q, np.int8), _c(K, np.int8), _c(V, np.int8)
     heads, Nq, d = Q.shape
@@ -177,11 +178,14 @@ def int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, p_quant=True, row_idx=No
     m = np.empty(n, np.float32)
     n_tie = np.zeros(n, np.int32)
     P = np.empty((n, N), np.int8) if want_P else None
+    if tie_flip is not None:
+        tie_flip = _c(tie_flip, np.uint64)
+        assert tie_flip.shape == (n,)
     if n:
         _load().orc_int_flash_attn_fwd(_p(Q), _p(K), _p(V), _p(sQ), _p(sK), _p(sV), 1, heads, Nq, N, d,
                                        int(bool(causal)), int(Bc), int(bool(p_quant)), int(sv_per_block),
                                        _p(row_idx), n, _p(O), _p(l), _p(m),
-                                       float(tie_rel), float(tie_abs), _p(n_tie), _p(P))
+                                       float(tie_rel), float(tie_abs), _p(n_tie), _p(P), _p(tie_flip))
     return {"O": O, "l": l, "m": m, "n_tie": n_tie, "P": P}
 
 
@@ -232,3 +236,42 @@ def attention_fp64(Q, K, V, causal=False, scale=1.0, row_idx=None):
         _load().orc_attention_fp64(_p(Q), _p(K), _p(V), heads, N, d, int(bool(causal)), float(scale),
                                    _p(row_idx), n, _p(O))
     return O
+
+
+def compare_up_to_ties(O_rows, Q, K, V, sQ, sK, sV, causal, Bc, row_idx=None, tie_rel=8 * 2.0 ** -24, tie_abs=2e-6,
+                       tol=1e-3):
+    """Compares O_rows [rows, d] (the implementation under test) with Algorithm 1 row by row.
+
+    Line 11 rounds 127 exp(S - m) to an integer on an fp32 argument; where that argument lies within fp32 evaluation
+    noise of a half-integer (tie_rel, tie_abs: see orc_int_flash_attn_fwd) either neighbour is a result of the
+    algorithm.  A row passes if it is within tol * max|O| of the oracle's output for SOME resolution of its flagged
+    entries: first the default one; for a row that misses it, the flagged entries are flipped one at a time
+    (greedily, each step re-evaluating the row in the oracle) until the row matches or no flip helps.
+    Returns a dict: err (per row, against the best resolution found), err_default (against the default one),
+    n_tie, flips (per row, number of entries flipped), scale (= max|O| of the default result), l."""
+    ref = int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, row_idx=row_idx, tie_rel=tie_rel, tie_abs=tie_abs)
+    O_ref = ref["O"].astype(np.float64)
+    got = np.asarray(O_rows, np.float64)
+    assert got.shape == O_ref.shape
+    scale = float(np.abs(O_ref).max())
+    err_default = np.abs(got - O_ref).max(axis=1)
+    err = err_default.copy()
+    flips = np.zeros(len(err), np.int32)
+    rows = np.arange(len(err), dtype=np.int64) if row_idx is None else _c(row_idx, np.int64)
+    for r in np.nonzero((err_default > tol * scale) & (ref["n_tie"] > 0))[0]:
+        k = int(min(ref["n_tie"][r], 64))
+        mask, best = np.uint64(0), err_default[r]
+        for _ in range(k):
+            cand = np.array([mask ^ np.uint64(1 << b) for b in range(k)], np.uint64)
+            alt = int_flash_attn_fwd(Q, K, V, sQ, sK, sV, causal, Bc, row_idx=np.full(k, rows[r], np.int64),
+                                     tie_rel=tie_rel, tie_abs=tie_abs, tie_flip=cand)["O"].astype(np.float64)
+            e = np.abs(alt - got[r]).max(axis=1)
+            b = int(e.argmin())
+            if e[b] >= best:
+                break
+            mask, best = cand[b], e[b]
+            if best <= tol * scale:
+                break
+        err[r] = best
+        flips[r] = bin(int(mask)).count("1")
+    return {"err": err, "err_default": err_default, "n_tie": ref["n_tie"], "flips": flips, "scale": scale, "l": ref["l"]}

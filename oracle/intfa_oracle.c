@@ -137,13 +137,18 @@ void orc_pv_i32(const int8_t *P, const int8_t *V, int64_t N, int d, int32_t *PV)
  *             the exponent argument moved by tie_rel * (|S| + |m|) + tie_abs; a different
  *             fp32 evaluation order may legitimately round those the other way.
  *   P_out     optional int8 [n_rows, N]: the rounded P of every key (p_quant = 1 only)
+ *   tie_flip  optional uint64 [n_rows]: bit k set = the k-th flagged near-tie entry of that row (in key order, k < 64)
+ *             takes the OTHER of its two neighbouring integers.  Line 11's round() is decided on an fp32 argument;
+ *             for a flagged entry a second, equally valid fp32 evaluation of that argument lands on the other side
+ *             of the half-integer, so both integers are results of Algorithm 1.  Used by the parity tests to check
+ *             that an output which differs from the default resolution is the output of another valid one.
  */
 void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                             const float *sQ, const float *sK, const float *sV,
                             int B, int H, int64_t Nq, int64_t N, int d, int causal, int Bc, int p_quant, int sv_per_block,
                             const int64_t *row_idx, int64_t n_rows,
                             float *O, float *l_out, float *m_out,
-                            double tie_rel, double tie_abs, int32_t *n_tie, int8_t *P_out)
+                            double tie_rel, double tie_abs, int32_t *n_tie, int8_t *P_out, const uint64_t *tie_flip)
 {
     const int64_t total = (int64_t)B * H * Nq;
     const int64_t shift = N - Nq;   /* causal: query i sees keys j <= i + shift (the last query sees every key) */
@@ -198,12 +203,16 @@ void orc_int_flash_attn_fwd(const int8_t *Q, const int8_t *K, const int8_t *V,
                         const float t = S[jj] - m_new;
                         const double u = (double)R_INT8 * exp((double)t);
                         P[jj] = (int32_t)nearbyint(u);
-                        psum += P[jj];
-                        if (n_tie) {
+                        if (n_tie || tie_flip) {
                             const double half = floor(u) + 0.5;
                             const double dt = tie_rel * (fabs((double)S[jj]) + fabs((double)m_new)) + tie_abs;
-                            if (fabs(u - half) <= u * dt) ++ties;
+                            if (fabs(u - half) <= u * dt) {
+                                if (tie_flip && ties < 64 && ((tie_flip[r] >> ties) & 1u))
+                                    P[jj] = (P[jj] == (int32_t)floor(u)) ? (int32_t)floor(u) + 1 : (int32_t)floor(u);
+                                ++ties;
+                            }
                         }
+                        psum += P[jj];
                         if (P_out) P_out[r * N + j0 + jj] = (int8_t)P[jj];
                     }
                     l = l * (float)alpha + (float)psum;            /* line 12 */

@@ -28,8 +28,7 @@ SIGNATURES = {
     "int_flash_attn_fwd_half": (_i, [_vp] * 5 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_half_rect": (_i, [_vp] * 5 + [_i] * 6 + [_vp, _i, _vp]),
     "ifa_block_cols_half": (_i, [_i, _i]),
-    "ifa_debug_qk_i32": (_i, [_vp, _vp, _i, _i, _vp]),
-    "ifa_debug_pv_i32": (_i, [_vp, _vp, _i, _i, _vp]),
+    "ifa_debug_fwd": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -181,21 +180,20 @@ def block_cols_half(d: int, causal: bool) -> int:
     return lib().ifa_block_cols_half(int(d), int(bool(causal)))
 
 
-def debug_qk_i32(Q_i8, K_i8):
+def debug_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, P_in=None, fill=-1):
+    """One head [N, d] through the production kernel with its integer stages written out.  Returns a dict with
+    S [N, N] int32, P [N, N] int8, PV [N / B_c, N, d] int32 and O [N, d] fp32; entries the kernel does not compute
+    (key tiles and blocks wholly above the causal diagonal) keep the value `fill`."""
     import torch
     N, d = Q_i8.shape
-    S = torch.empty((N, N), dtype=torch.int32, device=Q_i8.device)
-    L = lib()
-    L.ifa_set_stream(_stream())
-    _check(L.ifa_debug_qk_i32(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), N, d, _dev(S)), "ifa_debug_qk_i32")
-    return S
-
-
-def debug_pv_i32(P_i8, V_i8):
-    import torch
-    N, d = V_i8.shape
-    PV = torch.empty((N, d), dtype=torch.int32, device=V_i8.device)
-    L = lib()
-    L.ifa_set_stream(_stream())
-    _check(L.ifa_debug_pv_i32(_dev(P_i8, torch.int8), _dev(V_i8, torch.int8), N, d, _dev(PV)), "ifa_debug_pv_i32")
-    return PV
+    Bc = block_cols(d, causal)
+    dev = Q_i8.device
+    S = torch.full((N, N), fill, dtype=torch.int32, device=dev)
+    P = torch.full((N, N), fill, dtype=torch.int8, device=dev)
+    PV = torch.full((max(N // max(Bc, 1), 1), N, d), fill, dtype=torch.int32, device=dev)
+    O = torch.empty((N, d), dtype=torch.float32, device=dev)
+    _check(lib().ifa_debug_fwd(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8), _dev(s_Q, torch.float32),
+                               _dev(s_K, torch.float32), _dev(s_V, torch.float32), N, d, int(bool(causal)),
+                               None if P_in is None else _dev(P_in, torch.int8), _dev(S), _dev(P), _dev(PV), _dev(O), _stream()),
+           "ifa_debug_fwd")
+    return {"S": S, "P": P, "PV": PV, "O": O}

@@ -26,6 +26,18 @@
 // units and P = rint(exp2(acc * s_K * s_Q' - (m2 - log2 127))) with one v_exp_f32 per score and
 // v_cvt_pk_u8_f32 (round-half-even, measured) packing four P bytes per dword.
 //
+// Schedule of one key block (what the issue-model micro-benchmark under csrc/microbench measured to be the fastest
+// arrangement of this instruction mix on a gfx950 SIMD shared by two wavefronts):
+//     M1  the 16 MFMAs of S^T back to back, into four accumulators that then become the scores in place
+//     V1  scores: minus bias, times s_K, running maximum          (vector ALU only)
+//     P0  P of the first 32-key tile: fma, exp2, pack             (vector ALU + transcendental unit)
+//     M2  the 16 MFMAs of O^T, key tile by key tile into four accumulators, with the P work of the NEXT key tile
+//         between them, at raised wave priority: v_exp_f32 costs the issue port little while MFMAs are in flight
+//     --  wait for the staged copies, workgroup barrier, first K operands of the next block requested
+//     V3  the four accumulators folded into the running output
+// A wavefront in an MFMA stretch leaves the vector ALU to the other wavefront of its SIMD; on this chip an MFMA
+// and plain vector instructions issued by the SAME wavefront around it largely take turns instead of overlapping.
+//
 // The int32 results of both GEMMs are never converted: the accumulators start from a constant register block
 // holding the bit pattern of 1.5 * 2^23 (ACC_BIAS_I), so that a sum s reads as the float 1.5 * 2^23 + s, exactly,
 // and one fp32 subtraction recovers s.  The running output is kept negated so that its update is one three-address
@@ -39,6 +51,50 @@
 #include "intfa.h"
 #include "intfa_internal.h"
 #include "intfa_device.h"
+
+// experiment knobs (defaults are the shipped configuration)
+#ifndef IFA_PRIO
+#define IFA_PRIO 3
+#endif
+#ifndef IFA_PIN
+#define IFA_PIN 1
+#endif
+#ifndef IFA_MIDBAR
+#define IFA_MIDBAR 1
+#endif
+#ifndef IFA_QRELOAD_MT
+#define IFA_QRELOAD_MT 2
+#endif
+#ifndef IFA_KPRE
+#define IFA_KPRE 1
+#endif
+#ifndef IFA_PRIO_M1
+#define IFA_PRIO_M1 0
+#endif
+#ifndef IFA_STAGE_IN
+#define IFA_STAGE_IN 1   /* 1: staging copies issued in M1, 2: in V1 */
+#endif
+#ifndef IFA_PUP
+#define IFA_PUP 1        /* P tiles computed before the second GEMM starts */
+#endif
+#ifndef IFA_FAKE_K
+#define IFA_FAKE_K 0     /* timing-only: 1 = no K operand reads in M1 (wrong results) */
+#endif
+#ifndef IFA_FAKE_SK
+#define IFA_FAKE_SK 0    /* timing-only: 1 = no s_K reads in V1 (wrong results) */
+#endif
+#ifndef IFA_FAKE_V
+#define IFA_FAKE_V 0     /* timing-only: 1 = V operands read once per block only (wrong results) */
+#endif
+#ifndef IFA_STAMP
+#define IFA_STAMP 0
+#endif
+#if IFA_STAMP
+__device__ unsigned long long g_stamp[8];
+#define STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#endif
 
 namespace {
 
@@ -68,27 +124,17 @@ template <int D> __device__ __forceinline__ int v_swz(int row) {
     return (D == 128) ? s : (s & 3);
 }
 
-#if defined(__HIP_DEVICE_COMPILE__)   // device-only code: buffer resources and LDS builtins do not exist in the host pass
-// ---- staging: HBM -> LDS, asynchronous ------------------------------------------------------------
-// One direct-to-LDS 128-bit load moves 64 x 16 bytes: lane t's 16 bytes land at lds_base + 16 t.  The
-// LDS side is therefore fixed (1 KB contiguous per instruction) and the swizzle is applied on the
-// global side: the lane that fills slot p fetches the chunk that belongs there.  (This form, through the
-// compiler's builtin, serves the test hooks; the fused kernel issues its copies through lds_copy16.)
-template <int D, bool IS_V>
-__device__ __forceinline__ void stage_tile_async(const int8_t *__restrict__ gtile, lds_ptr tile, int wave, int lane) {
-    constexpr int CH = D / 16;
-    constexpr int ITER = BC * CH / THREADS;   // 1 KB pieces per wavefront
-#pragma unroll
-    for (int i = 0; i < ITER; ++i) {
-        const int piece = wave * ITER + i;
-        const int p = piece * 64 + lane;
-        const int row = p / CH, slot = p % CH;
-        const int c = slot ^ (IS_V ? v_swz<D>(row) : k_swz<D>(row));
-        __builtin_amdgcn_global_load_lds((const GLOBAL_AS void *)(gtile + row * D + 16 * c),
-                                         reinterpret_cast<LDS_AS void *>(tile + piece * 1024), 16, 0, 0);
-    }
-}
+// Test hook: where the int32 accumulators and the packed P of every key block go (null: not written), and an
+// optional P to use in place of the computed one.  Only the DBG instantiation of the kernel reads this.
+struct DebugDump {
+    int *S;                // [Nq, Nk] int32: Q_i8 K_i8^T, the accumulator of line 9 minus its starting constant
+    int8_t *P;             // [Nq, Nk] int8: P of line 11 as packed for the second GEMM
+    int *PV;               // [T_c, Nq, d] int32: P_j V_j of line 13 per key block, accumulator minus its starting constant
+    const int8_t *P_in;    // [Nq, Nk] int8 or null: replaces the computed P in the second GEMM (and in l)
+    int Nk;
+};
 
+#if defined(__HIP_DEVICE_COMPILE__)   // device-only code: buffer resources and LDS builtins do not exist in the host pass
 // Per-lane LDS byte offsets of the MFMA operands inside a K / V tile (tile- and block-independent).
 template <int D> struct LaneOffsets {
     // A operand of S^T = K Q^T, k-step kk: row r, chunk 2*kk + g.  The swizzle is an XOR on the chunk index and
@@ -169,34 +215,16 @@ __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int la
     if (wave >= 2) lds_copy4(nx.sk, nx.lsk + 256 * (wave - 2), 4 * lane + 256 * (wave - 2), nx.skoff);
 }
 
-// ---- the two MFMA tile products -----------------------------------------------------------------
-// S^T tile mt (keys 32*mt .. +31) x this wavefront's 32 queries, contraction over d.
-template <int D>
-__device__ __forceinline__ v16i gemm_kq_tile(lds_ptr ks, const LaneOffsets<D> &lo, const v4i (&qf)[D / 32], int mt) {
-    v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) {
-        const v4i a = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * mt * D);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qf[kk], acc, 0, 0, 0);
-    }
-    return acc;
-}
-
-// one k-step (32 keys of tile mt) of O^T tile dt
-template <int D>
-__device__ __forceinline__ v16i gemm_vp_step(lds_ptr vs, const LaneOffsets<D> &lo, v4i p, int dt, int mt, v16i acc) {
-    const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * mt * D));
-    const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * mt * D));
-    const v4i a = {t0[0], t0[1], t1[0], t1[1]};
-    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, p, acc, 0, 0, 0);
-}
-
 // ---- the fused kernel ---------------------------------------------------------------------------
 // Online-softmax state of one lane: one query row, half of the keys of every block.
 template <int D> struct RowState {
     float m2;             // running max in log2 units (identical in lanes r and r + 32)
     float l;              // running sum of the rounded P over this lane's keys
     float o[D / 32][16];  // MINUS the running output, d = 32*dt + 8*(v/4) + 4*g + v%4
+#if IFA_STAMP
+    unsigned long long t0;
+    unsigned ph[8];
+#endif
 };
 
 // Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: a block with masked keys --
@@ -206,86 +234,126 @@ template <int D> struct RowState {
 // lane of the wavefront; 32-key tiles after tile `last` (wave-uniform) are masked for every lane of
 // the wavefront and are skipped (their P is 0).  `wave` is wave-uniform.
 //
-// The source is software-pipelined: LDS operands of the next MFMA group are requested before the
-// current group is issued, and the VALU work on the previous 32-key tile follows the MFMAs of the
-// current one, so that neither LDS latency nor the MFMA-result latency is exposed.  Forcing a finer
-// MFMA/VALU interleave with scheduling barriers measured no better than the compiler's own order.
-template <int D, bool DIAG, bool VB>
-__device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, const LaneOffsets<D> &lo,
-                                              const v4i (&qf)[D / 32], float sq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
-                                              int g, float oscale, const Prefetch &nx, const v16i &bias, RowState<D> &st) {
+// !DIAG blocks also carry the block-to-block hand-over: they request the staging copies of the next block during
+// M1, wait for them and meet the workgroup barrier between M2 and V3 (by then this wavefront has read everything
+// it needs from the current buffers), and, if `preload_next`, request the first K operands of the next block right
+// after the barrier so that their LDS latency is covered by V3.  `kfirst` holds those operands on entry (when
+// `kfirst_valid`) and on exit.  DIAG blocks leave staging and barriers to the caller: a wavefront whose rows see
+// none of a masked block skips it altogether.
+template <int D, bool DIAG, bool VB, bool DBG>
+__device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, lds_ptr ks_next, const LaneOffsets<D> &lo,
+                                              v4i (&qf)[D / 32], const int8_t *__restrict__ qptr, float sq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
+                                              int g, float oscale, const Prefetch &nx, bool preload_next, const v16i &bias,
+                                              v4i (&kfirst)[IFA_KPRE][D / 32], RowState<D> &st, const DebugDump &dbg, long dbg_row, int dbg_j0, int dbg_jb, int dbg_nq) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
 
-    v4i kop[KS];
-    v4f skr[4];
+    auto load_k = [&](v4i (&dst)[KS], lds_ptr base, int mt) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) dst[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(base, lo, kk) + 32 * mt * D);
+    };
+    auto load_sk = [&](v4f (&dst)[4], int mt) {
+        if (IFA_FAKE_SK && !DIAG) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) dst[vq] = v4f{sq2, sq2 * 0.5f, sq2 * 0.25f, sq2};
+            return;
+        }
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) dst[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
+    };
+
+    // ---- M1: S^T = K Q^T, all four key tiles back to back (line 9, integer part).  The K operands of tile mt+1
+    // are requested before the MFMAs of tile mt are issued; the staging copies of the next block go out here too.
+    v16i sacc[4];
+    v4i kop[2][KS];
+    v4f skr[2][4];
+    constexpr int KPRE = DIAG ? 1 : IFA_KPRE;       // key tiles whose operands are in registers before the first MFMA
+    if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(IFA_PRIO_M1);
+    if (DIAG) load_k(kop[0], ks, 0);
+    else {
+#pragma unroll
+        for (int t = 0; t < KPRE; ++t)
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) kop[t][kk] = kfirst[t][kk];
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        if (mt <= last) {
+            if (KPRE == 1 && mt + 1 <= last && !(IFA_FAKE_K && !DIAG)) load_k(kop[(mt + 1) & 1], ks, mt + 1);
+            // the scales of the first two key tiles are requested under the last MFMAs, so that V1 starts on data
+            if (DIAG ? mt == last : mt == 2) load_sk(skr[0], 0);
+            if (DIAG ? (mt == last && last >= 1) : mt == 3) load_sk(skr[1], 1);
+            sacc[mt] = bias;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                sacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][kk], qf[kk], sacc[mt], 0, 0, 0);
+            if (KPRE == 2 && mt + 2 <= last) load_k(kop[mt & 1], ks, mt + 2);   // into the registers these MFMAs have read
+            if (!DIAG && IFA_PIN) {                                         // issue order: operand reads, then this tile's MFMAs
+                if (KPRE == 1) {
+                    if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 0 : KS, 0);
+                    else if (mt == 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 4 : KS + 4, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);
+                } else {
+                    if (mt >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);
+                    if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
+                }
+            }
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 1) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
+        }
+    }
+    if (!DIAG && IFA_STAGE_IN == 1) prefetch_sk(nx, wave, lane);
+    if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    STAMP(0);
+
+    if (DBG && dbg.S) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+            if (mt <= last)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = dbg_j0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (dbg_row < dbg_nq && key < dbg.Nk) dbg.S[dbg_row * dbg.Nk + key] = sacc[mt][v] - ACC_BIAS_I;
+                }
+    }
+
+    // ---- V1: line 9, fp32 part: a = acc * s_K in place of the accumulators (the positive per-row factor
+    // s_Q log2e is applied after the max), and the block maximum of line 10
     float a[4][16];
     float bmax = -INFINITY;
-
-    auto load_k = [&](int mt) {
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) kop[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * mt * D);
-    };
-    auto load_sk = [&](int mt) {
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) skr[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
-    };
-    // line 9, fp32 part: a = acc * s_K (the positive per-row factor s_Q log2e is applied after the max)
-    auto scale_elems = [&](int mt, const v16i &s, const v4f (&skv)[4], auto masked) {
+    auto scale_elems = [&](int mt, const v4f (&skv)[4], auto masked) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float x = (__int_as_float(s[4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
+                float x = (__int_as_float(sacc[mt][4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
                 if (decltype(masked)::value && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
                 bmax = fmaxf(bmax, x);
             }
     };
-    // only the tiles the mask boundary crosses pay for the comparisons (wave-uniform choice)
-    auto scale_tile = [&](int mt, const v16i &s, const v4f (&skv)[4]) {
-        if (DIAG && mt >= clear_tiles) scale_elems(mt, s, skv, std::true_type{});
-        else scale_elems(mt, s, skv, std::false_type{});
-    };
-
-    // ---- S^T = K Q^T, tile by tile; tile mt-1 is scaled while tile mt is in the matrix pipe.  One register set
-    // each for the K operands and the scales: the operands of tile mt+1 are requested right after the MFMAs of
-    // tile mt have been issued (they read their operands at issue), the scales of tile mt-1 just before them.
-    v16i sacc[2];
-    load_k(0);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         if (mt <= last) {
-            if (mt > 0) load_sk(mt - 1);
-            sacc[mt & 1] = bias;
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
-                sacc[mt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[kk], qf[kk], sacc[mt & 1], 0, 0, 0);
-            if (mt + 1 <= last) load_k(mt + 1);                  // into the registers the MFMAs above have read
-            if (mt > 0) scale_tile(mt - 1, sacc[(mt - 1) & 1], skr);
-            if (mt == last) load_sk(mt);
-            if (!DIAG && mt < KS) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
+            // only the tiles the mask boundary crosses pay for the comparisons (wave-uniform choice)
+            if (DIAG && mt >= clear_tiles) scale_elems(mt, skr[mt & 1], std::true_type{});
+            else scale_elems(mt, skr[mt & 1], std::false_type{});
+            if (mt + 2 <= last) load_sk(skr[mt & 1], mt + 2);    // into the registers this tile has just read
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
+            if (!DIAG && mt == 3 && IFA_STAGE_IN == 2) prefetch_sk(nx, wave, lane);
+            if (!DIAG && IFA_PIN) {                                         // 16 subtractions, 16 multiplies, 8 three-way maxima per tile
+                __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);
+                if (mt < 2 && !IFA_FAKE_SK) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            }
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
         }
     }
-    // transposing reads of the first V^T operands go out before the last tile is scaled
-    v4i vop[2][4];
-    auto load_v = [&](int buf, int dt) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            if (mt <= last) {
-                const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * mt * D));
-                const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * mt * D));
-                vop[buf][mt] = v4i{t0[0], t0[1], t1[0], t1[1]};
-            }
-        }
-    };
-    load_v(0, 0);
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-        if (mt == last) scale_tile(mt, sacc[mt & 1], skr);
+    if (!DIAG) __builtin_amdgcn_sched_barrier(0);
+    STAMP(1);
 
     // line 10
     bmax = pair_max(bmax);
@@ -294,59 +362,136 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     const float mm = m_new - LOG2_R;
     st.m2 = m_new;
 
-    // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order
+    // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order, one dword at a time
     v4i pf[4];
     uint32_t psum = 0;
+    auto p_dword = [&](int mt, int vq) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
+        if (DBG && dbg.P_in) {
+            const int key = dbg_j0 + 32 * mt + 8 * vq + 4 * g;
+            w = (dbg_row < dbg_nq && key + 3 < dbg.Nk) ? *reinterpret_cast<const uint32_t *>(dbg.P_in + dbg_row * dbg.Nk + key) : 0u;
+        }
+        psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
+        pf[mt][vq] = static_cast<int>(w);
+        if (DBG && dbg.P) {
+            const int key = dbg_j0 + 32 * mt + 8 * vq + 4 * g;
+            if (dbg_row < dbg_nq && key + 3 < dbg.Nk) *reinterpret_cast<uint32_t *>(dbg.P + dbg_row * dbg.Nk + key) = w;
+        }
+    };
+    // ---- P0
+#pragma unroll
+    for (int t = 0; t < IFA_PUP; ++t)
+        if (t <= last)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) p_dword(t, vq);
+    __builtin_amdgcn_sched_barrier(0);
+    STAMP(2);
+
+    // ---- M2: line 13, O^T = V^T P^T key tile by key tile into DT accumulators; between the MFMAs of key tile mt
+    // the P dwords of key tile mt + 1.  One V^T operand (two transposing reads) per MFMA, requested one key tile ahead
+    // into the registers the previous MFMA of that d tile has read.
+    v16i pacc[DT];
+    v4i vop[DT];
+    auto load_v = [&](int mt, int dt) {
+        const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * mt * D));
+        const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * mt * D));
+        vop[dt] = v4i{t0[0], t0[1], t1[0], t1[1]};
+    };
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) load_v(0, dt);
+    if (IFA_PRIO) __builtin_amdgcn_s_setprio(IFA_PRIO);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         if (mt <= last) {
+            if (!DIAG) __builtin_amdgcn_sched_barrier(0);
+            // The query operands are not kept across the second GEMM (the registers are needed for its four
+            // accumulators): they are fetched again here, two key tiles before the end of the block, and have
+            // landed by the wait in front of the barrier below.
+            if (!DIAG && mt == IFA_QRELOAD_MT) {
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                uint32_t w = 0;
+                for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
+                if (IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x020, KS, 0);
+            }
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
-                psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
-                pf[mt][vq] = static_cast<int>(w);
+            for (int dt = 0; dt < DT; ++dt) {
+                pacc[dt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt], pf[mt], mt == 0 ? bias : pacc[dt], 0, 0, 0);
+                if (!DIAG && IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (mt + 1 <= last) {
+                    if (!(IFA_FAKE_V && !DIAG)) load_v(mt + 1, dt);
+                    if (!DIAG && IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_V ? 0 : 2, 0);
+                }
+                if (mt + IFA_PUP <= last) {
+#pragma unroll
+                    for (int q = 0; q < 4 / DT; ++q) p_dword(mt + IFA_PUP, dt * (4 / DT) + q);
+                    if (!DIAG && IFA_PIN) {                                 // issue order: 4 fma, 4 exp2, 4 pack + row sum per dword
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4 * (4 / DT), 0);
+                        __builtin_amdgcn_sched_group_barrier(0x400, 4 * (4 / DT), 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 5 * (4 / DT), 0);
+                    }
+                }
             }
         }
     }
+    if (!DIAG) __builtin_amdgcn_sched_barrier(0);
+    if (IFA_PRIO) __builtin_amdgcn_s_setprio(0);
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
-    if (!DIAG) prefetch_sk(nx, wave, lane);
+    STAMP(3);
 
-    // line 13: O^T tile by tile; tile dt-1 is folded into O while tile dt is in the matrix pipe
-    v16i pacc[2];
-    // The running output is kept NEGATED: -O' = alpha (-O) - PV.  The negated addend needs the three-address
+    if (!DIAG && IFA_MIDBAR) {
+        wait_all_memory();                                       // my part of the next block has landed in LDS
+        STAMP(4);
+        __syncthreads();                                         // everyone's has, and the current buffers are free again
+        STAMP(5);
+        if (preload_next) {
+#pragma unroll
+            for (int t = 0; t < IFA_KPRE; ++t) load_k(kfirst[t], ks_next, t);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    if (DBG && dbg.PV) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (dbg_row < dbg_nq)
+                    dbg.PV[(static_cast<long>(dbg_jb) * dbg_nq + dbg_row) * D + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3)] = pacc[dt][v] - ACC_BIAS_I;
+    }
+
+    // ---- V3: the running output is kept NEGATED: -O' = alpha (-O) - PV.  The negated addend needs the three-address
     // v_fma_f32, whose result can go back to O's own register; with O = alpha O + PV the compiler picks the
     // two-address v_fmac_f32, the result lands in the converted-PV register and every element costs a copy.
     // With one V scale per key block the running output is kept in units of the current block's scale:
     // O/s_j = (alpha s_{j-1}/s_j) (O/s_{j-1}) + P V_j, so the per-block scale costs one scalar multiply per lane.
     const float alpha_o = VB ? alpha * oscale : alpha;
-    auto fold_o = [&](int dt, const v16i &pv) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(__int_as_float(pv[v]) - ACC_BIAS_F));
-
-    };
+            st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(__int_as_float(pacc[dt][v]) - ACC_BIAS_F));
+    STAMP(6);
+    if (!DIAG && !IFA_MIDBAR) {
+        wait_all_memory();
+        STAMP(4);
+        __syncthreads();
+        STAMP(5);
+        if (preload_next) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-        if (dt + 1 < DT) load_v((dt + 1) & 1, dt + 1);
-        pacc[dt & 1] = bias;
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-            if (mt <= last) pacc[dt & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt & 1][mt], pf[mt], pacc[dt & 1], 0, 0, 0);
-        if (dt > 0) fold_o(dt - 1, pacc[(dt - 1) & 1]);
+            for (int t = 0; t < IFA_KPRE; ++t) load_k(kfirst[t], ks_next, t);
+        }
     }
-    fold_o(DT - 1, pacc[(DT - 1) & 1]);
 }
 
 #endif  // __HIP_DEVICE_COMPILE__
 
-template <int D, bool CAUSAL, bool VB, typename OutT>
+template <int D, bool CAUSAL, bool VB, typename OutT, bool DBG = false>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
-    int heads, int Nq, int Nk, int head_group, OutT *__restrict__ O) {
+    int heads, int Nq, int Nk, int head_group, OutT *__restrict__ O, DebugDump dbg) {
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
@@ -365,6 +510,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const int q_head = qb * BR + q_local;                        // this lane's query inside the head
     // rows past Nq are computed on a clamped copy of the last row and never stored
     const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);
+    const long dbg_row = DBG ? q_head : 0;                       // the test hook runs one head
 
     const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
     const int8_t *Vh = V + static_cast<long>(head) * Nk * D;
@@ -381,10 +527,10 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(Nk) * 4);
 
     // line 5: Q_i and s_Q,i.  B operand: lane (r, g) holds bytes d = 32*kk + 16*g .. +15 of query r.
+    const int8_t *qptr = Q + qrow * D + 16 * g;
     v4i qf[D / 32];
 #pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk)
-        qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
+    for (int kk = 0; kk < D / 32; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
     const float sq2 = sQ[qrow] * LOG2E;
     const LaneOffsets<D> lo(lane, wave);
     {                                                            // line 8 for block 0
@@ -408,16 +554,27 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) st.o[dt][v] = 0.0f;
 
-    wait_all_memory();
-    __syncthreads();
-
     // Blocks in which every key counts for every query of the workgroup come first: all keys below Nk and, under
     // the mask, at or before the first query's last visible key.  The rest -- the block(s) the causal diagonal
     // crosses, the ragged last block -- run the masked code.
     const int nfull = min(nblocks, CAUSAL ? min(Nk / BC, (first_q + shift + 1) / BC) : Nk / BC);
+
+    wait_all_memory();
+    __syncthreads();
+    v4i kfirst[IFA_KPRE][D / 32];                                // K operands of the first key tile(s) of the coming block
+#pragma unroll
+    for (int t = 0; t < IFA_KPRE; ++t)
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk)
+            kfirst[t][kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(kbuf, lo, kk) + 32 * t * D);
+
     // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_c]
     const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
     float sv_prev = 1.0f;
+#if IFA_STAMP
+    for (int i = 0; i < 8; ++i) st.ph[i] = 0;
+    st.t0 = __builtin_readcyclecounter();
+#endif
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
         const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
@@ -427,10 +584,16 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const bool more = jb + 1 < nblocks;
         const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
                              vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
-        process_block<D, false, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, 0, 3, 4, g, oscale, pf, bias, st);
-        wait_all_memory();                                       // my part of the next block has landed in LDS
-        __syncthreads();                                         // everyone's has, and `cur` is free again
+        // the staged copies are awaited and the workgroup barrier is met inside, between the second GEMM and the fold
+        process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, qptr, sq2,
+                                         wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, bias, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
     }
+#if IFA_STAMP
+    if (lane == 0) {
+        for (int i = 0; i < 7; ++i) atomicAdd(&g_stamp[i], static_cast<unsigned long long>(st.ph[i]));
+        atomicAdd(&g_stamp[7], static_cast<unsigned long long>(nfull));
+    }
+#endif
     // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
     // ragged last block is one of them or, without a mask, the only one).  They are written out one after the
     // other rather than as a loop so that the staging offsets are dead once the second one has been requested.
@@ -447,7 +610,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
             const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
             const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
             sv_prev = sv_j;
-            process_block<D, true, VB>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, lo, qf, sq2, wave, lane, klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, bias, st);
+            process_block<D, true, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf, lo, qf, qptr, sq2, wave, lane,
+                                            klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, false, bias, kfirst, st, dbg,
+                                            dbg_row, j0, jb, Nq);
         }
     };
     if (nfull < nblocks) {
@@ -480,70 +645,6 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #endif
 }
 
-// ---- test hooks: the same tile code, accumulators written out -------------------------------------
-template <int D>
-__global__ __launch_bounds__(THREADS) void debug_qk_kernel(const int8_t *__restrict__ Q, const int8_t *__restrict__ K,
-                                                           int N, int *__restrict__ S) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    __shared__ Smem<D> sm;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
-    const long qrow = blockIdx.x * BR + 32 * wave + r;
-    const int j0 = blockIdx.y * BC;
-    const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
-    v4i qf[D / 32];
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk)
-        qf[kk] = *reinterpret_cast<const v4i *>(Q + qrow * D + 32 * kk + 16 * g);
-    const LaneOffsets<D> lo(lane, wave);
-    stage_tile_async<D, false>(K + static_cast<long>(j0) * D, kbuf, wave, lane);
-    wait_all_memory();
-    __syncthreads();
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const v16i s = gemm_kq_tile<D>(kbuf, lo, qf, mt);
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-            S[qrow * N + j0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3)] = s[v];
-    }
-#endif
-}
-
-template <int D>
-__global__ __launch_bounds__(THREADS) void debug_pv_kernel(const int8_t *__restrict__ P, const int8_t *__restrict__ V,
-                                                           int N, int *__restrict__ PV) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    __shared__ Smem<D> sm;
-    constexpr int DT = D / 32;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 31, g = lane >> 5;
-    const long qrow = blockIdx.x * BR + 32 * wave + r;
-    const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
-    const LaneOffsets<D> lo(lane, wave);
-    v16i acc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) acc[dt] = v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    for (int j0 = 0; j0 < N; j0 += BC) {
-        __syncthreads();
-        stage_tile_async<D, true>(V + static_cast<long>(j0) * D, vbuf, wave, lane);
-        wait_all_memory();
-        __syncthreads();
-        v4i pf[4];                                   // the layout the fused kernel builds in registers
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq)
-                pf[mt][vq] = *reinterpret_cast<const int *>(P + qrow * N + j0 + 32 * mt + 8 * vq + 4 * g);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) acc[dt] = gemm_vp_step<D>(vbuf, lo, pf[mt], dt, mt, acc[dt]);
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) PV[qrow * D + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3)] = acc[dt][v];
-#endif
-}
-
 // ---- host side ----------------------------------------------------------------------------------
 hipStream_t g_stream = nullptr;
 
@@ -552,7 +653,8 @@ int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *s
                int heads, int Nq, int Nk, void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((Nq + BR - 1) / BR);
     hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, VB, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0,
-                       st, Q, K, V, sQ, sK, sV, heads, Nq, Nk, head_group_for(CAUSAL, 2L * Nk * D, (Nq + BR - 1) / BR), static_cast<OutT *>(O));
+                       st, Q, K, V, sQ, sK, sV, heads, Nq, Nk, head_group_for(CAUSAL, 2L * Nk * D, (Nq + BR - 1) / BR), static_cast<OutT *>(O),
+                       DebugDump{nullptr, nullptr, nullptr, nullptr, 0});
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
@@ -653,28 +755,41 @@ extern "C" int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_
     return int_flash_attn_fwd_ex(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, N, d, causal, O, IFA_F16, g_stream);
 }
 
-extern "C" int ifa_debug_qk_i32(const signed char *Q_i8, const signed char *K_i8, int N, int d, int *S_i32) {
-    if (!Q_i8 || !K_i8 || !S_i32) return IFA_ERR_NULL;
-    if (N <= 0 || d <= 0) return IFA_ERR_SHAPE;
-    if ((d != 64 && d != 128) || N % BR != 0 || N > 32768) return IFA_ERR_UNSUPPORTED;
-    if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || (reinterpret_cast<uintptr_t>(S_i32) & 3)) return IFA_ERR_UNSUPPORTED;
-    const int8_t *Q = reinterpret_cast<const int8_t *>(Q_i8);
-    const int8_t *K = reinterpret_cast<const int8_t *>(K_i8);
-    const dim3 grid(N / BR, N / BC);
-    if (d == 128) hipLaunchKernelGGL(debug_qk_kernel<128>, grid, dim3(THREADS), 0, g_stream, Q, K, N, S_i32);
-    else hipLaunchKernelGGL(debug_qk_kernel<64>, grid, dim3(THREADS), 0, g_stream, Q, K, N, S_i32);
+// Test hook: the production kernel (the DBG instantiation differs only by the stores below the accumulators)
+// on one head, with the integer stages written out.
+template <int D, bool CAUSAL>
+static int launch_debug(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV, int N,
+                 const DebugDump &dbg, float *O, hipStream_t st) {
+    hipLaunchKernelGGL((int_flash_attn_fwd_kernel<D, CAUSAL, false, float, true>), dim3(N / BR), dim3(THREADS), 0, st, Q, K, V, sQ, sK,
+                       sV, 1, N, N, 1, O, dbg);
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
-extern "C" int ifa_debug_pv_i32(const signed char *P_i8, const signed char *V_i8, int N, int d, int *PV_i32) {
-    if (!P_i8 || !V_i8 || !PV_i32) return IFA_ERR_NULL;
+extern "C" int ifa_debug_fwd(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8, const float *s_Q,
+                             const float *s_K, const float *s_V, int N, int d, int causal, const signed char *P_in, int *S_i32,
+                             signed char *P_i8, int *PV_i32, float *O, void *hip_stream) {
+    if (!Q_i8 || !K_i8 || !V_i8 || !s_Q || !s_K || !s_V || !O) return IFA_ERR_NULL;
     if (N <= 0 || d <= 0) return IFA_ERR_SHAPE;
-    if ((d != 64 && d != 128) || N % BR != 0 || N > 32768) return IFA_ERR_UNSUPPORTED;
-    if (!ifa_aligned16(P_i8) || !ifa_aligned16(V_i8) || (reinterpret_cast<uintptr_t>(PV_i32) & 3)) return IFA_ERR_UNSUPPORTED;
-    const int8_t *P = reinterpret_cast<const int8_t *>(P_i8);
+    if ((d != 64 && d != 128) || N % BR != 0 || N > 8192) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
+        (reinterpret_cast<uintptr_t>(S_i32) & 3) || (reinterpret_cast<uintptr_t>(PV_i32) & 3) ||
+        (reinterpret_cast<uintptr_t>(P_in) & 3) || (reinterpret_cast<uintptr_t>(P_i8) & 3) ||
+        (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) || (reinterpret_cast<uintptr_t>(s_V) & 3))
+        return IFA_ERR_UNSUPPORTED;
+    const int8_t *Q = reinterpret_cast<const int8_t *>(Q_i8);
+    const int8_t *K = reinterpret_cast<const int8_t *>(K_i8);
     const int8_t *V = reinterpret_cast<const int8_t *>(V_i8);
-    const dim3 grid(N / BR);
-    if (d == 128) hipLaunchKernelGGL(debug_pv_kernel<128>, grid, dim3(THREADS), 0, g_stream, P, V, N, PV_i32);
-    else hipLaunchKernelGGL(debug_pv_kernel<64>, grid, dim3(THREADS), 0, g_stream, P, V, N, PV_i32);
-    return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+    const DebugDump dbg = {S_i32, reinterpret_cast<int8_t *>(P_i8), PV_i32, reinterpret_cast<const int8_t *>(P_in), N};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (d == 128)
+        return causal ? launch_debug<128, true>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st) : launch_debug<128, false>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st);
+    return causal ? launch_debug<64, true>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st) : launch_debug<64, false>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st);
 }
+
+#if IFA_STAMP
+extern "C" int ifa_debug_read_stamps(unsigned long long *out8, int reset) {
+    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_stamp), 64) != hipSuccess) return IFA_ERR_HIP;
+    if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 64) != hipSuccess) return IFA_ERR_HIP; }
+    return IFA_OK;
+}
+#endif

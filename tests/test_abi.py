@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_qk_i32", "ifa_debug_pv_i32", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -98,8 +98,8 @@ def test_argument_validation_happens_on_the_host(L):
     assert hf(p, p, p, p, p, 1, 1, 1 << 29, 128, 0, p, 1, None) == -4   # one head of fp16 V must stay below 2 GiB
     assert hf(p, p, p, p, p, 1, 1, 0x7ff00000 // 256 + 1, 128, 0, p, 1, None) == -4   # first N past that limit
     assert L.int_flash_attn_fwd_half_rect(p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4   # causal with Nk < Nq
-    assert L.ifa_debug_qk_i32(p, p, 100, 128, p) == -4
-    assert L.ifa_debug_pv_i32(p, null, 128, 128, p) == -1
+    assert L.ifa_debug_fwd(p, p, p, p, p, p, 100, 128, 0, null, p, p, p, p, null) == -4
+    assert L.ifa_debug_fwd(p, null, p, p, p, p, 128, 128, 0, null, p, p, p, p, null) == -1
 
 
 def test_bench_refuses_more_than_one_gpu():

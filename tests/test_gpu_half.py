@@ -251,9 +251,14 @@ def _full_size(ifa, name, full_heads, rows_per_head):
 
 @pytest.mark.timeout(600)
 def test_c3_full_size_sampled_rows(ifa):
-    _full_size(ifa, "c3", full_heads=1, rows_per_head=32)
+    _full_size(ifa, "c3", full_heads=2, rows_per_head=64)
 
 
 @pytest.mark.timeout(600)
 def test_c5_full_size_sampled_rows(ifa):
-    _full_size(ifa, "c5", full_heads=1, rows_per_head=64)
+    _full_size(ifa, "c5", full_heads=2, rows_per_head=64)
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size_sampled_rows(ifa):
+    _full_size(ifa, "c4", full_heads=2, rows_per_head=64)

@@ -1,8 +1,12 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the same
 seeded inputs.  Bit-exact for the quantizers and the int32 GEMM accumulators; for O the bar is
-max|O_gpu - O_oracle| <= 1e-3 * max|O_oracle| (the benchmark spec's tolerance), plus, for the few rows where
-the oracle reports a P entry within fp32 evaluation noise of a rounding boundary, the exact effect one
-such entry rounding the other way can have on that row (either rounding is a valid Algorithm-1 result)."""
+max|O_gpu - O_oracle| <= 1e-3 * max|O_oracle| on EVERY row, where O_oracle is the oracle's output for a valid
+resolution of line 11's rounding: P entries whose fp32 argument lies within evaluation noise of a half-integer may
+round either way (the hardware exp2 against the oracle's correctly rounded exp is enough to decide them
+differently), and ONE such entry moves a row of O by up to |V_j - O_i| s_V / l -- percents of max|O| for a sharp
+row.  A row that misses the oracle's default resolution must therefore match the oracle re-run with some of its
+flagged entries rounded the other way (oracle.compare_up_to_ties); rows without flagged entries have no such way
+out.  The number of rows that needed it is printed."""
 import math
 
 import numpy as np
@@ -142,19 +146,81 @@ def test_quantize_workload_heads_bit_exact(ifa):
 
 # ------------------------------------------------------------------ int32 accumulators: bit-exact
 
-@pytest.mark.parametrize("N,d", [(128, 64), (128, 128), (384, 128), (256, 64)])
-def test_int32_gemm_accumulators_bit_exact(ifa, N, d):
-    rng = np.random.default_rng(N + d)
-    Q = rng.integers(-128, 128, (N, d), dtype=np.int8)
-    K = rng.integers(-128, 128, (N, d), dtype=np.int8)
-    V = rng.integers(-128, 128, (N, d), dtype=np.int8)
-    P = rng.integers(0, 128, (N, N), dtype=np.int8)
-    Q[0] = 127; K[1] = 127; K[2] = -128; Q[3] = -128          # extremes of the accumulator range
-    P[5] = 127; V[:, 7] = -128
-    S = ifa.debug_qk_i32(dev(Q), dev(K)).cpu().numpy()
-    assert np.array_equal(S, oracle.qk_i32(Q, K))
-    PV = ifa.debug_pv_i32(dev(P), dev(V)).cpu().numpy()
-    assert np.array_equal(PV, oracle.pv_i32(P, V))
+def _oracle_block_pv(P, V, Bc):
+    """P_j V_j per key block with the oracle's integer GEMM: [N / Bc, N, d] int32."""
+    N = P.shape[0]
+    out = []
+    for j in range(N // Bc):
+        Pj = np.zeros_like(P)
+        Pj[:, j * Bc:(j + 1) * Bc] = P[:, j * Bc:(j + 1) * Bc]
+        out.append(oracle.pv_i32(Pj, V))
+    return np.stack(out)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(128, 64), (128, 128), (384, 128), (256, 64), (640, 128)])
+def test_int32_accumulators_of_the_production_kernel_bit_exact(ifa, N, d, causal):
+    # The fused kernel itself (its test instantiation stores what sits in its accumulators): the int32 result of
+    # line 9, the packed P of line 11 and the int32 result of line 13 per key block, against the oracle's integer
+    # GEMMs -- bit for bit.  P is compared with the oracle's own P outside the entries it flags as near-ties.
+    rng = np.random.default_rng(N + d + causal)
+    Q = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    K = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    V = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    Q[0] = 127; K[1] = 127; K[2] = -128; Q[3] = -128; V[:, 7] = -128       # extremes of the accumulator range of line 9
+    base = 1.0 / (73.3 * 73.3 * math.sqrt(d))
+    sQ = (rng.uniform(0.5, 1.5, N) * math.sqrt(base)).astype(np.float32)
+    sK = (rng.uniform(0.5, 1.5, N) * math.sqrt(base)).astype(np.float32)
+    sV = np.array([0.01], np.float32)
+    Bc = ifa.block_cols(d, causal)
+    out = ifa.debug_fwd(dev(Q), dev(K), dev(V), dev(sQ), dev(sK), dev(sV), causal=causal, fill=-1)
+    torch.cuda.synchronize()
+    S, P, PV, O = (out[k].cpu().numpy() for k in ("S", "P", "PV", "O"))
+    ref = oracle.int_flash_attn_fwd(Q[None], K[None], V[None], sQ[None], sK[None], sV, causal, Bc, tie_rel=TIE_REL, tie_abs=TIE_ABS,
+                                    want_P=True)
+    S_ref = oracle.qk_i32(Q, K)
+    seen = np.ones((N, N), bool) if not causal else np.tril(np.ones((N, N), bool))   # keys a query sees
+    assert np.array_equal(S[seen], S_ref[seen])                                        # line 9, exact
+    # P: every visible entry was written (0..127), masked entries of visited tiles are 0, and it is the oracle's P
+    # except where the oracle itself says the rounding is within fp32 noise of a tie (then off by at most one)
+    assert P[seen].min() >= 0
+    P_ref = ref["P"]
+    diff = np.abs(P[seen].astype(np.int32) - P_ref[seen].astype(np.int32))
+    assert diff.max() <= 1
+    rows_with_diff = np.unique(np.nonzero((np.abs(P.astype(np.int32) - P_ref.astype(np.int32)) * seen) > 0)[0])
+    assert np.all(ref["n_tie"][rows_with_diff] > 0), "P differs from the oracle in a row without a flagged near-tie"
+    # line 13, exact: the kernel's P_j V_j against the oracle's integer GEMM on the kernel's own P
+    Pk = np.where(seen & (P >= 0), P, 0).astype(np.int8)
+    PV_ref = _oracle_block_pv(Pk, V, Bc)
+    for j in range(N // Bc):
+        rows = np.arange(N) if not causal else np.arange(j * Bc, N)                     # query blocks that visit block j
+        assert np.array_equal(PV[j][rows], PV_ref[j][rows]), f"P V of key block {j}"
+    # and the output of the same launch is the production output
+    O_prod = run_gpu(ifa, Q[None], K[None], V[None], sQ[None], sK[None], sV, 1, 1, causal).cpu().numpy().reshape(N, d)
+    assert np.array_equal(O, O_prod)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_second_gemm_accumulator_extremes_with_injected_p(ifa, d):
+    # P = 127 everywhere against V = -127 / +127 columns drives |P_j V_j| to 127 * 127 * 128, the end of the range
+    # the accumulator's starting constant leaves room for; random P in between.  P is injected in place of the
+    # computed one, everything else is the production path.
+    N = 256
+    rng = np.random.default_rng(d)
+    Q = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    K = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    V = rng.integers(-127, 128, (N, d), dtype=np.int8)
+    P_in = rng.integers(0, 128, (N, N), dtype=np.int8)
+    P_in[5] = 127; P_in[6] = 127; V[:, 7] = -127; V[:, 9] = 127; P_in[200] = 0
+    ones = np.ones(N, np.float32)
+    out = ifa.debug_fwd(dev(Q), dev(K), dev(V), dev(ones * 1e-4), dev(ones), dev(np.array([1.0], np.float32)), causal=False, P_in=dev(P_in))
+    torch.cuda.synchronize()
+    Bc = ifa.block_cols(d, False)
+    PV = out["PV"].cpu().numpy()
+    assert np.array_equal(out["P"].cpu().numpy(), P_in)
+    assert np.array_equal(PV, _oracle_block_pv(P_in, V, Bc))
+    assert PV.min() == -127 * 127 * Bc and PV.max() == 127 * 127 * Bc
+    assert np.array_equal(out["S"].cpu().numpy(), oracle.qk_i32(Q, K))
 
 
 # ------------------------------------------------------------------ Algorithm 1 end to end
@@ -171,28 +237,23 @@ def run_gpu(ifa, Qq, Kq, Vq, sQ, sK, sV, B, H, causal, out_dtype=None):
 
 
 def check_against_oracle(ifa, O_gpu_rows, Qq, Kq, Vq, sQ, sK, sV, causal, row_idx=None, label="", quiet=False):
+    """Asserts |O_gpu - O_oracle| <= 1e-3 max|O_oracle| on every row, O_oracle being Algorithm 1 with a valid
+    resolution of its near-tie roundings (see the module docstring)."""
     d = Qq.shape[-1]
     Bc = ifa.block_cols(d, causal)
-    ref = oracle.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal, Bc, row_idx=row_idx,
-                                    tie_rel=TIE_REL, tie_abs=TIE_ABS)
-    O_ref = ref["O"]
-    assert O_gpu_rows.shape == O_ref.shape
     assert np.all(np.isfinite(O_gpu_rows))
-    scale = np.abs(O_ref).max()
-    err = np.abs(O_gpu_rows.astype(np.float64) - O_ref).max(axis=1)
-    heads_of_rows = (np.arange(O_ref.shape[0]) if row_idx is None else row_idx) // Qq.shape[1]
-    n_tie = ref["n_tie"].astype(np.float64)
-    # one P entry rounding the other way moves O[i, c] by |V_jc - O_ic| s_V / (l +- 1) <= 2*127*s_V / (l - n)
-    sV_head = sV.max(axis=1) if sV.ndim == 2 else sV          # per-block scales: the largest bounds any block
-    slack = n_tie * 2 * 127.0 * sV_head[heads_of_rows] / np.maximum(ref["l"] - n_tie, 1.0)
-    clean = n_tie == 0
+    res = oracle.compare_up_to_ties(O_gpu_rows, Qq, Kq, Vq, sQ, sK, sV, causal, Bc, row_idx=row_idx,
+                                    tie_rel=TIE_REL, tie_abs=TIE_ABS, tol=TOL)
+    err, scale, clean = res["err"], res["scale"], res["n_tie"] == 0
     worst_clean = (err[clean].max() / scale) if clean.any() else 0.0
+    resolved = int((res["flips"] > 0).sum())
     if not quiet:
         print(f"[parity {label}] rows={len(err)} max|dO|/max|O|={err.max() / scale:.3e} "
-              f"(rows without near-ties: {worst_clean:.3e}, rows with near-ties: {int((~clean).sum())})", flush=True)
-    assert np.all(err <= TOL * scale + slack), (err.max() / scale, int((err > TOL * scale + slack).sum()))
-    assert worst_clean <= TOL
-    return err.max() / scale, worst_clean, int((~clean).sum()), len(err)
+              f"(rows without near-ties: {worst_clean:.3e}; rows with near-ties: {int((~clean).sum())}, of which "
+              f"{resolved} match the oracle with flagged entries rounded the other way, "
+              f"worst before that {res['err_default'].max() / scale:.3e})", flush=True)
+    assert np.all(err <= TOL * scale), (err.max() / scale, int((err > TOL * scale).sum()), int((~clean).sum()))
+    return err.max() / scale, worst_clean, resolved, len(err)
 
 
 @pytest.mark.parametrize("scaled", [False, True])
@@ -441,7 +502,7 @@ def test_degenerate_inputs(ifa):
     # tiny and huge scales stay finite
     O = run_gpu(ifa, Qq, Kq, Vq, sQ * np.float32(1e-6), sK, sV * np.float32(1e4), 1, 1, False).cpu().numpy()
     assert np.all(np.isfinite(O))
-    check_against_oracle(ifa, run_gpu(ifa, Qq, Kq, Vq, sQ * 40, sK, sV, 1, 1, True).cpu().numpy().reshape(N, d),
+    check_against_oracle(ifa, run_gpu(ifa, Qq, Kq, Vq, sQ * 40, sK, sV, 1, 1, True).cpu().numpy().reshape(N, d),  # x40: sharp rows
                          Qq, Kq, Vq, sQ * 40, sK, sV, True, label="sharp")
 
 
@@ -543,15 +604,18 @@ def test_blockwise_v_scales_improve_heavy_tailed_accuracy(ifa):
 
 # ------------------------------------------------------------------ full-size workloads, sampled rows
 
-def _full_size(ifa, name, scaled, full_heads, rows_per_head):
+def _full_size(ifa, name, scaled, full_heads, rows_per_head, vblock=False):
+    """The whole workload through the launch configuration bench.py times; the oracle on every row of the first
+    `full_heads` heads and `rows_per_head` seeded rows of every other head.  vblock: one V scale per key block."""
     w = workloads.WORKLOADS[name]
+    Bc = ifa.block_cols(w.d, w.causal)
     sh = (w.B, w.H, w.N, w.d)
     Qd = torch.empty(sh, dtype=torch.int8, device="cuda")
     Kd = torch.empty_like(Qd)
     Vd = torch.empty_like(Qd)
     sQd = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
     sKd = torch.empty_like(sQd)
-    sVd = torch.empty((w.B, w.H), dtype=torch.float32, device="cuda")
+    sVd = torch.empty((w.B, w.H, (w.N + Bc - 1) // Bc) if vblock else (w.B, w.H), dtype=torch.float32, device="cuda")
     sample = workloads.sample_rows(w, full_heads, rows_per_head)
     kept = {}
     fold = np.float32(1.0 / math.sqrt(w.d)) if scaled else np.float32(1.0)
@@ -559,11 +623,12 @@ def _full_size(ifa, name, scaled, full_heads, rows_per_head):
         x = quantized_inputs(w, heads=[h])
         sq = (x["sQ"] * fold).astype(np.float32)
         b, hh = divmod(h, w.H)
+        Vq, sv = oracle.quantize_blockwise(x["V"], Bc) if vblock else (x["Vq"], x["sV"])
         Qd[b, hh].copy_(torch.from_numpy(x["Qq"][0])); Kd[b, hh].copy_(torch.from_numpy(x["Kq"][0]))
-        Vd[b, hh].copy_(torch.from_numpy(x["Vq"][0]))
+        Vd[b, hh].copy_(torch.from_numpy(Vq[0]))
         sQd[b, hh].copy_(torch.from_numpy(sq[0])); sKd[b, hh].copy_(torch.from_numpy(x["sK"][0]))
-        sVd[b, hh] = float(x["sV"][0])
-        kept[h] = (x["Qq"][0], x["Kq"][0], x["Vq"][0], sq[0], x["sK"][0], x["sV"][0])
+        sVd[b, hh] = torch.from_numpy(np.asarray(sv[0], np.float32))
+        kept[h] = (x["Qq"][0], x["Kq"][0], Vq[0], sq[0], x["sK"][0], np.asarray(sv[0], np.float32))
     out_dtype = torch.float32                                  # parity on the fp32 result; casts are tested above
     O = ifa.int_flash_attn_fwd(Qd, Kd, Vd, sQd, sKd, sVd, causal=w.causal, out_dtype=out_dtype)
     torch.cuda.synchronize()
@@ -575,23 +640,28 @@ def _full_size(ifa, name, scaled, full_heads, rows_per_head):
         b, hh = divmod(h, w.H)
         got = O[b, hh].cpu().numpy()[rows]
         r = check_against_oracle(ifa, got, Qq[None], Kq[None], Vq[None], sq[None], sk[None],
-                                 np.array([sv], np.float32), w.causal, row_idx=rows, quiet=True)
+                                 sv.reshape(1, -1) if vblock else sv.reshape(1), w.causal, row_idx=rows, quiet=True)
         worst, worst_clean, ties, n = max(worst, r[0]), max(worst_clean, r[1]), ties + r[2], n + r[3]
-    print(f"[parity {name} scaled={scaled}] sampled rows={n} max|dO|/max|O| per head={worst:.3e} "
-          f"(rows without near-ties: {worst_clean:.3e}, rows with near-ties: {ties})", flush=True)
+    print(f"[parity {name} scaled={scaled} vblock={vblock}] sampled rows={n} max|dO|/max|O| per head={worst:.3e} "
+          f"(rows without near-ties: {worst_clean:.3e}, rows matched with flagged entries rounded the other way: {ties})", flush=True)
 
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("scaled", [True, False])
 def test_c3_full_size_sampled_rows(ifa, scaled):
-    _full_size(ifa, "c3", scaled, full_heads=1, rows_per_head=32)
+    _full_size(ifa, "c3", scaled, full_heads=2, rows_per_head=64)
 
 
 @pytest.mark.timeout(600)
 def test_c5_full_size_sampled_rows(ifa):
-    _full_size(ifa, "c5", True, full_heads=1, rows_per_head=64)
+    _full_size(ifa, "c5", True, full_heads=2, rows_per_head=64)
 
 
 @pytest.mark.timeout(900)
 def test_c4_full_size_sampled_rows(ifa):
-    _full_size(ifa, "c4", True, full_heads=1, rows_per_head=16)
+    _full_size(ifa, "c4", True, full_heads=2, rows_per_head=64)
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size_sampled_rows_blockwise_v_scales(ifa):
+    _full_size(ifa, "c4", True, full_heads=2, rows_per_head=64, vblock=True)

@@ -380,3 +380,54 @@ def test_rectangular_rows_are_rows_of_the_square_problem(Bc):
     # first of the Nq causal rows sees exactly N - Nq + 1 keys
     P0 = oracle.int_flash_attn_fwd(Qq[:, N - Nq:], Kq, Vq, sQ[:, N - Nq:], sK, sV, True, Bc, want_P=True)["P"][0]
     assert not P0[N - Nq + 1:].any()
+
+
+def test_forced_tie_resolution_by_hand():
+    # One query, two keys, one block.  S = [0, -x] with x = fp32(ln 2): 127 exp(-x) = 63.4999999 lies 1e-7 below the
+    # half-integer 63.5, so line 11 gives P = [127, 63] and the entry is flagged as a near-tie; resolved the other
+    # way it is 64.  With V = [100, -50] and s_V = 1 line 16 gives (127*100 - 63*50) / 190 = 50.2631578...
+    # and, flipped, (127*100 - 64*50) / 191 = 49.7382198...
+    Q = np.array([[[1]]], np.int8); K = np.array([[[0], [-1]]], np.int8); V = np.array([[[100], [-50]]], np.int8)
+    sQ = np.ones((1, 1), np.float32); sK = np.array([[1.0, np.float32(np.log(2.0))]], np.float32); sV = np.ones(1, np.float32)
+    kw = dict(tie_rel=8 * 2.0 ** -24, tie_abs=2e-6, want_P=True)
+    r0 = oracle.int_flash_attn_fwd(Q, K, V, sQ, sK, sV, False, 128, **kw)
+    assert r0["n_tie"][0] == 1 and r0["P"].tolist() == [[127, 63]]
+    assert abs(r0["O"][0, 0] - 9550.0 / 190.0) < 1e-5
+    r1 = oracle.int_flash_attn_fwd(Q, K, V, sQ, sK, sV, False, 128, tie_flip=np.array([1], np.uint64), **kw)
+    assert r1["P"].tolist() == [[127, 64]] and abs(r1["O"][0, 0] - 9500.0 / 191.0) < 1e-5 and r1["l"][0] == 191.0
+    r2 = oracle.int_flash_attn_fwd(Q, K, V, sQ, sK, sV, False, 128, tie_flip=np.array([2], np.uint64), **kw)   # no second tie
+    assert r2["P"].tolist() == [[127, 63]] and r2["O"][0, 0] == r0["O"][0, 0]
+    # an entry that is not near a half-integer is never flipped: x = 1 gives 127 / e = 46.72
+    sK2 = np.array([[1.0, 1.0]], np.float32)
+    r3 = oracle.int_flash_attn_fwd(Q, K, V, sQ, sK2, sV, False, 128, tie_flip=np.array([1], np.uint64), **kw)
+    assert r3["n_tie"][0] == 0 and r3["P"].tolist() == [[127, 47]]
+
+
+def test_compare_up_to_ties_accepts_the_other_valid_result_and_nothing_else():
+    Q = np.array([[[1]]], np.int8); K = np.array([[[0], [-1]]], np.int8); V = np.array([[[100], [-50]]], np.int8)
+    sQ = np.ones((1, 1), np.float32); sK = np.array([[1.0, np.float32(np.log(2.0))]], np.float32); sV = np.ones(1, np.float32)
+    args = (Q, K, V, sQ, sK, sV, False, 128)
+    same = oracle.compare_up_to_ties(np.array([[9550.0 / 190.0]]), *args)
+    assert same["err"][0] < 1e-5 and same["flips"][0] == 0
+    other = oracle.compare_up_to_ties(np.array([[9500.0 / 191.0]]), *args)          # the entry rounded the other way
+    assert other["err_default"][0] > 0.5 and other["err"][0] < 1e-5 and other["flips"][0] == 1
+    wrong = oracle.compare_up_to_ties(np.array([[50.0]]), *args)                    # between the two: neither result
+    assert wrong["err"][0] > 0.2
+    # a larger random problem compared with itself: nothing to resolve, zero error
+    rng = np.random.default_rng(3)
+    Qr, Kr, Vr = (rng.integers(-127, 128, (2, 256, 64), dtype=np.int8) for _ in range(3))
+    sq = rng.uniform(0.002, 0.004, (2, 256)).astype(np.float32); sk = rng.uniform(0.002, 0.004, (2, 256)).astype(np.float32)
+    sv = np.array([0.01, 0.02], np.float32)
+    O = oracle.int_flash_attn_fwd(Qr, Kr, Vr, sq, sk, sv, True, 128)["O"]
+    res = oracle.compare_up_to_ties(O, Qr, Kr, Vr, sq, sk, sv, True, 128)
+    assert res["err"].max() == 0.0 and res["flips"].sum() == 0
+    # ... and with one row replaced by the result of flipping its first flagged entry (if it has one)
+    ref = oracle.int_flash_attn_fwd(Qr, Kr, Vr, sq, sk, sv, True, 128, tie_rel=8 * 2.0 ** -24, tie_abs=2e-6)
+    flagged = np.nonzero(ref["n_tie"] > 0)[0]
+    if flagged.size:
+        r = int(flagged[0])
+        alt = oracle.int_flash_attn_fwd(Qr, Kr, Vr, sq, sk, sv, True, 128, row_idx=np.array([r]), tie_rel=8 * 2.0 ** -24,
+                                        tie_abs=2e-6, tie_flip=np.array([1], np.uint64))["O"]
+        O2 = O.copy(); O2[r] = alt[0]
+        res2 = oracle.compare_up_to_ties(O2, Qr, Kr, Vr, sq, sk, sv, True, 128, tol=1e-7)
+        assert res2["err"].max() <= 1e-7 * res2["scale"] and res2["flips"][r] == 1
