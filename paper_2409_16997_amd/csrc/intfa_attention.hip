@@ -86,12 +86,22 @@
 #ifndef IFA_FAKE_V
 #define IFA_FAKE_V 0     /* timing-only: 1 = V operands read once per block only (wrong results) */
 #endif
+#ifndef IFA_FAKE_STAGE
+#define IFA_FAKE_STAGE 0 /* timing-only: 1 = no staging copies in the block loop (stale LDS contents, wrong results) */
+#endif
 #ifndef IFA_STAMP
 #define IFA_STAMP 0
 #endif
 #if IFA_STAMP
-__device__ unsigned long long g_stamp[8];
+__device__ unsigned long long g_stamp[16];
+#ifndef IFA_LDS_PAD
+#define IFA_LDS_PAD 0    /* timing-only: extra LDS bytes per workgroup (forces one workgroup per CU) */
+#endif
+#if IFA_STAMP == 1
 #define STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
+#else   /* 2: only the whole-kernel clock stamps */
+#define STAMP(i) do { } while (0)
+#endif
 #else
 #define STAMP(i) do { } while (0)
 #endif
@@ -220,7 +230,7 @@ __device__ __forceinline__ void prefetch_sk(const Prefetch &nx, int wave, int la
 template <int D> struct RowState {
     float m2;             // running max in log2 units (identical in lanes r and r + 32)
     float l;              // running sum of the rounded P over this lane's keys
-    float o[D / 32][16];  // MINUS the running output, d = 32*dt + 8*(v/4) + 4*g + v%4
+    float o[D / 32][16];  // the running output in units of 2^26, d = 32*dt + 8*(v/4) + 4*g + v%4
 #if IFA_STAMP
     unsigned long long t0;
     unsigned ph[8];
@@ -242,8 +252,8 @@ template <int D> struct RowState {
 // none of a masked block skips it altogether.
 template <int D, bool DIAG, bool VB, bool DBG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, lds_ptr ks_next, const LaneOffsets<D> &lo,
-                                              v4i (&qf)[D / 32], const int8_t *__restrict__ qptr, float sq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
-                                              int g, float oscale, const Prefetch &nx, bool preload_next, const v16i &bias,
+                                              const v4i (&qf)[D / 32], float nq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
+                                              int g, float oscale, const Prefetch &nx, bool preload_next,
                                               v4i (&kfirst)[IFA_KPRE][D / 32], RowState<D> &st, const DebugDump &dbg, long dbg_row, int dbg_j0, int dbg_jb, int dbg_nq) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
@@ -255,7 +265,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     auto load_sk = [&](v4f (&dst)[4], int mt) {
         if (IFA_FAKE_SK && !DIAG) {
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) dst[vq] = v4f{sq2, sq2 * 0.5f, sq2 * 0.25f, sq2};
+            for (int vq = 0; vq < 4; ++vq) { dst[vq] = v4f{nq2, nq2 * 0.5f, nq2 * 0.25f, nq2}; asm volatile("" : "+v"(dst[vq])); }
             return;
         }
 #pragma unroll
@@ -283,27 +293,31 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             // the scales of the first two key tiles are requested under the last MFMAs, so that V1 starts on data
             if (DIAG ? mt == last : mt == 2) load_sk(skr[0], 0);
             if (DIAG ? (mt == last && last >= 1) : mt == 3) load_sk(skr[1], 1);
-            sacc[mt] = bias;
+            sacc[mt] = mfma_i8_start(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][0], qf[0]);
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
+            for (int kk = 1; kk < KS; ++kk)
                 sacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][kk], qf[kk], sacc[mt], 0, 0, 0);
+            if (IFA_FAKE_K && !DIAG) {
+#pragma unroll
+                for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+v"(kop[0][kk]));
+            }
             if (KPRE == 2 && mt + 2 <= last) load_k(kop[mt & 1], ks, mt + 2);   // into the registers these MFMAs have read
             if (!DIAG && IFA_PIN) {                                         // issue order: operand reads, then this tile's MFMAs
                 if (KPRE == 1) {
                     if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 0 : KS, 0);
                     else if (mt == 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 4 : KS + 4, 0);
                     else __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS - 1, 0);
                 } else {
                     if (mt >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, KS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS - 1, 0);
                     if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
                 }
             }
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 1) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 1 && !IFA_FAKE_STAGE) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
         }
     }
-    if (!DIAG && IFA_STAGE_IN == 1) prefetch_sk(nx, wave, lane);
+    if (!DIAG && IFA_STAGE_IN == 1 && !IFA_FAKE_STAGE) prefetch_sk(nx, wave, lane);
     if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     STAMP(0);
@@ -315,23 +329,24 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = dbg_j0 + 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-                    if (dbg_row < dbg_nq && key < dbg.Nk) dbg.S[dbg_row * dbg.Nk + key] = sacc[mt][v] - ACC_BIAS_I;
+                    if (dbg_row < dbg_nq && key < dbg.Nk) dbg.S[dbg_row * dbg.Nk + key] = sacc[mt][v] - ACC_START_I;
                 }
     }
 
-    // ---- V1: line 9, fp32 part: a = acc * s_K in place of the accumulators (the positive per-row factor
-    // s_Q log2e is applied after the max), and the block maximum of line 10
+    // ---- V1: line 9, fp32 part, in place of the accumulators.  t = ACC_START_F - acc = -(Q K^T) 2^-26 exactly, and
+    // a = t * s_K: MINUS the score in units of 2^26 / (s_Q log2e); the per-row factor (negative: nq2) is applied after
+    // the extremum, so the block maximum of line 10 is a minimum here and a masked key is +infinity.
     float a[4][16];
-    float bmax = -INFINITY;
+    float bmin = INFINITY;
     auto scale_elems = [&](int mt, const v4f (&skv)[4], auto masked) {
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float x = (__int_as_float(sacc[mt][4 * vq + e]) - ACC_BIAS_F) * skv[vq][e];
-                if (decltype(masked)::value && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = -INFINITY;   // masked key
+                float x = (ACC_START_F - __int_as_float(sacc[mt][4 * vq + e])) * skv[vq][e];
+                if (decltype(masked)::value && (32 * mt + 8 * vq + 4 * g + e > klimit)) x = INFINITY;   // masked key
                 a[mt][4 * vq + e] = x;
-                bmax = fmaxf(bmax, x);
+                bmin = fminf(bmin, x);
             }
     };
 #pragma unroll
@@ -343,21 +358,21 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             if (mt + 2 <= last) load_sk(skr[mt & 1], mt + 2);    // into the registers this tile has just read
             if (!DIAG && mt < KS && IFA_STAGE_IN == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
             if (!DIAG && mt == 3 && IFA_STAGE_IN == 2) prefetch_sk(nx, wave, lane);
-            if (!DIAG && IFA_PIN) {                                         // 16 subtractions, 16 multiplies, 8 three-way maxima per tile
+            if (!DIAG && IFA_PIN) {                                         // 16 subtractions, 16 multiplies, 8 three-way minima per tile
                 __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);
                 if (mt < 2 && !IFA_FAKE_SK) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             }
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
+            for (int v = 0; v < 16; ++v) a[mt][v] = INFINITY;
         }
     }
     if (!DIAG) __builtin_amdgcn_sched_barrier(0);
     STAMP(1);
 
     // line 10
-    bmax = pair_max(bmax);
-    const float m_new = fmaxf(st.m2, bmax * sq2);
+    bmin = pair_min(bmin);
+    const float m_new = fmaxf(st.m2, bmin * nq2);
     const float alpha = __builtin_amdgcn_exp2f(st.m2 - m_new);   // exp2(-inf) = 0 on the first block
     const float mm = m_new - LOG2_R;
     st.m2 = m_new;
@@ -369,7 +384,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         uint32_t w = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], sq2, -mm)), e, w);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm)), e, w);
         if (DBG && dbg.P_in) {
             const int key = dbg_j0 + 32 * mt + 8 * vq + 4 * g;
             w = (dbg_row < dbg_nq && key + 3 < dbg.Nk) ? *reinterpret_cast<const uint32_t *>(dbg.P_in + dbg_row * dbg.Nk + key) : 0u;
@@ -407,20 +422,13 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     for (int mt = 0; mt < 4; ++mt) {
         if (mt <= last) {
             if (!DIAG) __builtin_amdgcn_sched_barrier(0);
-            // The query operands are not kept across the second GEMM (the registers are needed for its four
-            // accumulators): they are fetched again here, two key tiles before the end of the block, and have
-            // landed by the wait in front of the barrier below.
-            if (!DIAG && mt == IFA_QRELOAD_MT) {
-#pragma unroll
-                for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
-                if (IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x020, KS, 0);
-            }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
-                pacc[dt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt], pf[mt], mt == 0 ? bias : pacc[dt], 0, 0, 0);
-                if (!DIAG && IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                pacc[dt] = mt == 0 ? mfma_i8_start(vop[dt], pf[0]) : __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt], pf[mt], pacc[dt], 0, 0, 0);
+                if (!DIAG && IFA_PIN && mt > 0) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (mt + 1 <= last) {
                     if (!(IFA_FAKE_V && !DIAG)) load_v(mt + 1, dt);
+                    else asm volatile("" : "+v"(vop[dt]));
                     if (!DIAG && IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_V ? 0 : 2, 0);
                 }
                 if (mt + IFA_PUP <= last) {
@@ -458,12 +466,13 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 if (dbg_row < dbg_nq)
-                    dbg.PV[(static_cast<long>(dbg_jb) * dbg_nq + dbg_row) * D + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3)] = pacc[dt][v] - ACC_BIAS_I;
+                    dbg.PV[(static_cast<long>(dbg_jb) * dbg_nq + dbg_row) * D + 32 * dt + 8 * (v >> 2) + 4 * g + (v & 3)] = pacc[dt][v] - ACC_START_I;
     }
 
-    // ---- V3: the running output is kept NEGATED: -O' = alpha (-O) - PV.  The negated addend needs the three-address
-    // v_fma_f32, whose result can go back to O's own register; with O = alpha O + PV the compiler picks the
-    // two-address v_fmac_f32, the result lands in the converted-PV register and every element costs a copy.
+    // ---- V3: the running output is kept in units of 2^26: with t = ACC_START_F - acc = -(P V) 2^-26, exactly (one
+    // v_sub_f32 with the inline constant), O' = alpha O - t is one fused multiply-add.  The negated addend needs the
+    // three-address v_fma_f32, whose result can go back to O's own register; with a plain addend the compiler picks the
+    // two-address v_fmac_f32, the result lands in t's register and every element costs a copy.
     // With one V scale per key block the running output is kept in units of the current block's scale:
     // O/s_j = (alpha s_{j-1}/s_j) (O/s_{j-1}) + P V_j, so the per-block scale costs one scalar multiply per lane.
     const float alpha_o = VB ? alpha * oscale : alpha;
@@ -471,7 +480,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(__int_as_float(pacc[dt][v]) - ACC_BIAS_F));
+            st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(ACC_START_F - __int_as_float(pacc[dt][v])));
     STAMP(6);
     if (!DIAG && !IFA_MIDBAR) {
         wait_all_memory();
@@ -495,6 +504,14 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
+#if IFA_STAMP
+    const unsigned long long k_c0 = __builtin_readcyclecounter(), k_w0 = __builtin_amdgcn_s_memrealtime();
+#if IFA_LDS_PAD
+    __shared__ int lds_pad[IFA_LDS_PAD / 4];
+    if (Nq < 0) lds_pad[threadIdx.x] = Nk;     // never true: keeps the array allocated
+    if (Nq < -1) O[0] = static_cast<OutT>(static_cast<float>(lds_pad[threadIdx.x ^ 1]));
+#endif
+#endif
 
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
@@ -531,7 +548,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     v4i qf[D / 32];
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
-    const float sq2 = sQ[qrow] * LOG2E;
+    const float nq2 = sQ[qrow] * (-LOG2E * ACC_UNIT);        // line 9's s_Q, log2 e, the accumulator unit and the sign of a
     const LaneOffsets<D> lo(lane, wave);
     {                                                            // line 8 for block 0
         const Prefetch first = {rK, rV, rSK, 0, 0, kbuf, vbuf, skbuf};
@@ -539,11 +556,6 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(first, lo, wave, i); prefetch_v_piece<D>(first, lo, wave, i); }
         prefetch_sk(first, wave, lane);
     }
-
-    v16i bias;                                                   // 16 registers that stay constant: the MFMAs never write them
-#pragma unroll
-    for (int v = 0; v < 16; ++v) bias[v] = ACC_BIAS_I;
-    asm volatile("" : "+v"(bias));                               // opaque: kept in registers, not re-materialised per use
 
     // line 6
     RowState<D> st;
@@ -585,13 +597,16 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
                              vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
         // the staged copies are awaited and the workgroup barrier is met inside, between the second GEMM and the fold
-        process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, qptr, sq2,
-                                         wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, bias, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
+        process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, nq2,
+                                         wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
     }
 #if IFA_STAMP
     if (lane == 0) {
         for (int i = 0; i < 7; ++i) atomicAdd(&g_stamp[i], static_cast<unsigned long long>(st.ph[i]));
         atomicAdd(&g_stamp[7], static_cast<unsigned long long>(nfull));
+        atomicAdd(&g_stamp[8], __builtin_readcyclecounter() - k_c0);
+        atomicAdd(&g_stamp[9], __builtin_amdgcn_s_memrealtime() - k_w0);
+        atomicAdd(&g_stamp[10], 1ull);
     }
 #endif
     // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
@@ -610,8 +625,8 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
             const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
             const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
             sv_prev = sv_j;
-            process_block<D, true, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf, lo, qf, qptr, sq2, wave, lane,
-                                            klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, false, bias, kfirst, st, dbg,
+            process_block<D, true, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf, lo, qf, nq2, wave, lane,
+                                            klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, false, kfirst, st, dbg,
                                             dbg_row, j0, jb, Nq);
         }
     };
@@ -634,7 +649,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 
     // lines 15-17: O_i = diag(l)^-1 O s_V.  Lane (r, g) holds d = 32*dt + 8*(v/4) + 4*g + v%4.
     const float l = st.l + swap32(st.l);
-    const float f = -(VB ? sv_prev : sVh[0]) / l;                // st.o holds -O (in units of the last block's scale if VB)
+    const float f = (VB ? sv_prev : sVh[0]) * ACC_UNIT / l;      // st.o holds O 2^-26 (in units of the last block's scale if VB)
     // The buffers the last block did not use are free for every wavefront since the barrier before it: each
     // wavefront stages its tile in its own 64 D bytes of them and stores whole (fp32: half) rows.
     const int freeb = nblocks & 1;
@@ -787,9 +802,9 @@ extern "C" int ifa_debug_fwd(const signed char *Q_i8, const signed char *K_i8, c
 }
 
 #if IFA_STAMP
-extern "C" int ifa_debug_read_stamps(unsigned long long *out8, int reset) {
-    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_stamp), 64) != hipSuccess) return IFA_ERR_HIP;
-    if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 64) != hipSuccess) return IFA_ERR_HIP; }
+extern "C" int ifa_debug_read_stamps(unsigned long long *out16, int reset) {
+    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_stamp), 128) != hipSuccess) return IFA_ERR_HIP;
+    if (reset) { unsigned long long z[16] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 128) != hipSuccess) return IFA_ERR_HIP; }
     return IFA_OK;
 }
 #endif

@@ -27,6 +27,14 @@ constexpr float LOG2E = 1.44269504088896340736f;
 // costs twice a subtraction on this chip).  |Q K^T| <= 128 * 128 * 128 = 2^21 and |P V| <= 128 * 127 * 128 < 2^21.
 constexpr int ACC_BIAS_I = 0x4B400000;
 constexpr float ACC_BIAS_F = 12582912.0f;
+// The INT8 kernel goes one step further: its accumulators start at the bit pattern of 1 / (2 pi), 0x3E22F983, which the
+// MFMA takes as an INLINE constant (no registers hold it).  That float sits 2291075 steps above the bottom of its
+// binade [2^-3, 2^-2), where one step is 2^-26: a sum s in [-2291075, 6097532] reads as 1 / (2 pi) + s 2^-26 exactly,
+// and (1 / (2 pi)) - acc = -s 2^-26 is one v_sub_f32 with an inline constant operand (4-byte encoding).
+// |Q K^T| <= 128^3 = 2097152 and |P V| <= 127 * 128 * 128 = 2080768 for B_c = 128 both fit.
+constexpr int ACC_START_I = 0x3E22F983;
+constexpr float ACC_START_F = 0.15915494309189532f;   // rounds to 0x3E22F983
+constexpr float ACC_UNIT = 67108864.0f;               // 2^26: accumulator steps per unit of the float view
 
 // Heads an XCD works on at a time (measured on MI355X over group sizes 1 .. 32; the default 4 is never far off).
 // Without the mask every workgroup of a head walks all of its K and V, and what a group streams at a time should fit
@@ -100,10 +108,25 @@ __device__ __forceinline__ float uniform(float x) {
     return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
 }
 
-// max over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
+// First MFMA of an accumulation chain: D = A B + ACC_START_I in every element, the constant being the instruction's
+// inline operand 1 / (2 pi).  Written as assembly because the compiler folds a constant accumulator into the
+// instruction only when that constant has a single use; otherwise it parks it in 16 registers.  The result is only
+// ever read by the next MFMA of the chain (same registers as its accumulator, which may follow back to back).
+__device__ __forceinline__ v16i mfma_i8_start(const v4i &a, const v4i &b) {
+    v16i d;
+    asm("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(d) : "v"(a), "v"(b));
+    return d;
+}
+
+// max (min) over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
 __device__ __forceinline__ float pair_max(float x) {
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+__device__ __forceinline__ float pair_min(float x) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fminf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
 #endif  // __HIP_DEVICE_COMPILE__
