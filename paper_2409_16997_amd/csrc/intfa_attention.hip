@@ -72,10 +72,13 @@
 #define IFA_PRIO_M1 0
 #endif
 #ifndef IFA_STAGE_IN
-#define IFA_STAGE_IN 1   /* 1: staging copies issued in M1, 2: in V1 */
+#define IFA_STAGE_IN 1   /* staging copies issued 1: in M1, 2: in V1, 3: K pieces in V1 and V pieces early in M2, 4: K in M1, V in V1 */
 #endif
 #ifndef IFA_PUP
 #define IFA_PUP 1        /* P tiles computed before the second GEMM starts */
+#endif
+#ifndef IFA_PACK
+#define IFA_PACK 1       /* P to bytes: 0 = four v_cvt_pk_u8_f32 per dword, 1 = two v_cvt_pknorm_u16_f32 and one v_perm_b32 */
 #endif
 #ifndef IFA_FAKE_K
 #define IFA_FAKE_K 0     /* timing-only: 1 = no K operand reads in M1 (wrong results) */
@@ -93,17 +96,25 @@
 #define IFA_STAMP 0
 #endif
 #if IFA_STAMP
-__device__ unsigned long long g_stamp[16];
+__device__ unsigned long long g_stamp[32];
+constexpr int STAMP_WAVES = 1 << 17;                       // per-wavefront records of the last launch: no atomics on the way out
+__device__ unsigned g_wave_rec[STAMP_WAVES][12];
 #ifndef IFA_LDS_PAD
 #define IFA_LDS_PAD 0    /* timing-only: extra LDS bytes per workgroup (forces one workgroup per CU) */
 #endif
-#if IFA_STAMP == 1
+#if IFA_STAMP == 3   /* fine stamps inside M1 */
+#define STAMP2(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph2[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
+#else
+#define STAMP2(i) do { } while (0)
+#endif
+#if IFA_STAMP == 1 || IFA_STAMP == 3
 #define STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
 #else   /* 2: only the whole-kernel clock stamps */
 #define STAMP(i) do { } while (0)
 #endif
 #else
 #define STAMP(i) do { } while (0)
+#define STAMP2(i) do { } while (0)
 #endif
 
 namespace {
@@ -112,6 +123,7 @@ using namespace ifa_dev;
 
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
 [[maybe_unused]] constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
+[[maybe_unused]] constexpr float LOG2_R_NORM = -9.01129329928057f;        // log2(127 / 65535)
 
 template <int D> struct Smem {
     alignas(4096) int8_t k[2][BC * D];   // K_j, row = key, 16-byte slots XOR-swizzled by row
@@ -234,6 +246,7 @@ template <int D> struct RowState {
 #if IFA_STAMP
     unsigned long long t0;
     unsigned ph[8];
+    unsigned ph2[12];
 #endif
 };
 
@@ -293,6 +306,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             // the scales of the first two key tiles are requested under the last MFMAs, so that V1 starts on data
             if (DIAG ? mt == last : mt == 2) load_sk(skr[0], 0);
             if (DIAG ? (mt == last && last >= 1) : mt == 3) load_sk(skr[1], 1);
+            if (!DIAG) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt); }
             sacc[mt] = mfma_i8_start(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][0], qf[0]);
 #pragma unroll
             for (int kk = 1; kk < KS; ++kk)
@@ -314,10 +328,15 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
                     if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
                 }
             }
+            if (!DIAG && IFA_STAMP == 3) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt + 1); }
             if (!DIAG && mt < KS && IFA_STAGE_IN == 1 && !IFA_FAKE_STAGE) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
+            if (!DIAG && (mt & 1) == 0 && IFA_STAGE_IN == 1 && IFA_FAKE_STAGE == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }   // timing-only: half of the copies
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 4) prefetch_k_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 5) prefetch_v_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && IFA_STAMP == 3) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt + 2); }
         }
     }
-    if (!DIAG && IFA_STAGE_IN == 1 && !IFA_FAKE_STAGE) prefetch_sk(nx, wave, lane);
+    if (!DIAG && (IFA_STAGE_IN == 1 || IFA_STAGE_IN == 4 || IFA_STAGE_IN == 5) && !IFA_FAKE_STAGE) prefetch_sk(nx, wave, lane);
     if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     STAMP(0);
@@ -357,7 +376,10 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             else scale_elems(mt, skr[mt & 1], std::false_type{});
             if (mt + 2 <= last) load_sk(skr[mt & 1], mt + 2);    // into the registers this tile has just read
             if (!DIAG && mt < KS && IFA_STAGE_IN == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
-            if (!DIAG && mt == 3 && IFA_STAGE_IN == 2) prefetch_sk(nx, wave, lane);
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 3) prefetch_k_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 4) prefetch_v_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && mt < KS && IFA_STAGE_IN == 5) prefetch_k_piece<D>(nx, lo, wave, mt);
+            if (!DIAG && mt == 3 && (IFA_STAGE_IN == 2 || IFA_STAGE_IN == 3)) prefetch_sk(nx, wave, lane);
             if (!DIAG && IFA_PIN) {                                         // 16 subtractions, 16 multiplies, 8 three-way minima per tile
                 __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);
                 if (mt < 2 && !IFA_FAKE_SK) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -374,7 +396,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     bmin = pair_min(bmin);
     const float m_new = fmaxf(st.m2, bmin * nq2);
     const float alpha = __builtin_amdgcn_exp2f(st.m2 - m_new);   // exp2(-inf) = 0 on the first block
-    const float mm = m_new - LOG2_R;
+    const float mm = m_new - (IFA_PACK == 0 ? LOG2_R : LOG2_R_NORM);
     st.m2 = m_new;
 
     // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order, one dword at a time
@@ -382,9 +404,21 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     uint32_t psum = 0;
     auto p_dword = [&](int mt, int vq) {
         uint32_t w = 0;
+        if (IFA_PACK == 0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm)), e, w);
+            for (int e = 0; e < 4; ++e)
+                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm)), e, w);
+        } else {
+            // The exponent carries log2(127 / 65535), so that the value is P / 65535 and the conversion to a 16-bit
+            // normalised integer rounds it to P (to nearest; measured): two conversions give the four P of this dword in
+            // bytes 0 and 2 of two registers, one byte permute gathers them -- three half-rate instructions for four.
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm));
+            typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+            const us2 lo = __builtin_amdgcn_cvt_pknorm_u16(x[0], x[1]), hi = __builtin_amdgcn_cvt_pknorm_u16(x[2], x[3]);
+            w = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x06040200u);
+        }
         if (DBG && dbg.P_in) {
             const int key = dbg_j0 + 32 * mt + 8 * vq + 4 * g;
             w = (dbg_row < dbg_nq && key + 3 < dbg.Nk) ? *reinterpret_cast<const uint32_t *>(dbg.P_in + dbg_row * dbg.Nk + key) : 0u;
@@ -426,6 +460,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             for (int dt = 0; dt < DT; ++dt) {
                 pacc[dt] = mt == 0 ? mfma_i8_start(vop[dt], pf[0]) : __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt], pf[mt], pacc[dt], 0, 0, 0);
                 if (!DIAG && IFA_PIN && mt > 0) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (!DIAG && IFA_STAGE_IN == 3 && mt == 0 && dt < KS) prefetch_v_piece<D>(nx, lo, wave, dt);
                 if (mt + 1 <= last) {
                     if (!(IFA_FAKE_V && !DIAG)) load_v(mt + 1, dt);
                     else asm volatile("" : "+v"(vop[dt]));
@@ -437,7 +472,7 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
                     if (!DIAG && IFA_PIN) {                                 // issue order: 4 fma, 4 exp2, 4 pack + row sum per dword
                         __builtin_amdgcn_sched_group_barrier(0x002, 4 * (4 / DT), 0);
                         __builtin_amdgcn_sched_group_barrier(0x400, 4 * (4 / DT), 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 5 * (4 / DT), 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (IFA_PACK == 0 ? 5 : 4) * (4 / DT), 0);
                     }
                 }
             }
@@ -456,6 +491,11 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         if (preload_next) {
 #pragma unroll
             for (int t = 0; t < IFA_KPRE; ++t) load_k(kfirst[t], ks_next, t);
+        }
+        if (IFA_STAGE_IN == 6) {     // the buffers of this block are free: the block after next goes there, a whole block ahead of its use
+#pragma unroll
+            for (int i = 0; i < KS; ++i) { prefetch_k_piece<D>(nx, lo, wave, i); prefetch_v_piece<D>(nx, lo, wave, i); }
+            prefetch_sk(nx, wave, lane);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -555,6 +595,13 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #pragma unroll
         for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(first, lo, wave, i); prefetch_v_piece<D>(first, lo, wave, i); }
         prefetch_sk(first, wave, lane);
+        if (IFA_STAGE_IN == 6) {                                 // ... and for block 1 (a request past the last block fetches nothing)
+            const bool two = nblocks > 1;
+            const Prefetch second = {rK, rV, rSK, two ? BC * D : NOWHERE, two ? BC * 4 : NOWHERE, kbuf + BC * D, vbuf + BC * D, skbuf + BC * 4};
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(second, lo, wave, i); prefetch_v_piece<D>(second, lo, wave, i); }
+            prefetch_sk(second, wave, lane);
+        }
     }
 
     // line 6
@@ -585,6 +632,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     float sv_prev = 1.0f;
 #if IFA_STAMP
     for (int i = 0; i < 8; ++i) st.ph[i] = 0;
+    for (int i = 0; i < 12; ++i) st.ph2[i] = 0;
     st.t0 = __builtin_readcyclecounter();
 #endif
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
@@ -592,22 +640,19 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
         const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
         sv_prev = sv_j;
-        const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
-        const bool more = jb + 1 < nblocks;
-        const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
-                             vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
+        // line 8, asynchronous: for the next block into the other buffers, or (IFA_STAGE_IN == 6) for the block after next
+        // into this block's own buffers once the barrier inside has freed them
+        const int ahead = IFA_STAGE_IN == 6 ? 2 : 1, dst = IFA_STAGE_IN == 6 ? cur : nxt;
+        const int j1 = (jb + ahead) * BC;
+        const bool more = jb + ahead < nblocks;
+        const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + dst * BC * D,
+                             vbuf + dst * BC * D, skbuf + dst * BC * 4};
         // the staged copies are awaited and the workgroup barrier is met inside, between the second GEMM and the fold
         process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, nq2,
                                          wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
     }
 #if IFA_STAMP
-    if (lane == 0) {
-        for (int i = 0; i < 7; ++i) atomicAdd(&g_stamp[i], static_cast<unsigned long long>(st.ph[i]));
-        atomicAdd(&g_stamp[7], static_cast<unsigned long long>(nfull));
-        atomicAdd(&g_stamp[8], __builtin_readcyclecounter() - k_c0);
-        atomicAdd(&g_stamp[9], __builtin_amdgcn_s_memrealtime() - k_w0);
-        atomicAdd(&g_stamp[10], 1ull);
-    }
+    const unsigned long long k_c1 = __builtin_readcyclecounter(), k_w1 = __builtin_amdgcn_s_memrealtime();   // end of the main loop
 #endif
     // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
     // ragged last block is one of them or, without a mask, the only one).  They are written out one after the
@@ -632,7 +677,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     };
     if (nfull < nblocks) {
         const bool second = nfull + 1 < nblocks;
-        if (second) {                                            // line 8 for the second masked block
+        if (second && IFA_STAGE_IN != 6) {                       // line 8 for the second masked block
             const int nxt = (nfull & 1) ^ 1, j1 = (nfull + 1) * BC;
             const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
 #pragma unroll
@@ -652,11 +697,30 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const float f = (VB ? sv_prev : sVh[0]) * ACC_UNIT / l;      // st.o holds O 2^-26 (in units of the last block's scale if VB)
     // The buffers the last block did not use are free for every wavefront since the barrier before it: each
     // wavefront stages its tile in its own 64 D bytes of them and stores whole (fp32: half) rows.
+    if (IFA_STAGE_IN == 6) {   // requests past the last block (they move no tensor data) may still be in flight into these buffers
+        wait_all_memory();
+        __syncthreads();
+    }
     const int freeb = nblocks & 1;
     const lds_ptr stage = (wave < 2 ? kbuf : vbuf) + freeb * BC * D + (wave & 1) * (64 * D);
     const int row0 = qb * BR + 32 * wave;                        // first query row of this wavefront
     OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
     store_tile_staged<D, OutT>(stage, orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
+#if IFA_STAMP
+    {
+        const unsigned long long k_c2 = __builtin_readcyclecounter(), k_w2 = __builtin_amdgcn_s_memrealtime();
+        const long wid = static_cast<long>(blockIdx.x) * 4 + wave;
+        if (lane == 0 && wid < STAMP_WAVES) {
+            unsigned *r = g_wave_rec[wid];
+            for (int i = 0; i < 7; ++i) r[i] = st.ph[i];
+            r[7] = static_cast<unsigned>(nfull);
+            r[8] = static_cast<unsigned>(k_c2 - k_c0);          // whole kernel, cycles
+            r[9] = static_cast<unsigned>(k_w2 - k_w0);          // whole kernel, 100 MHz ticks
+            r[10] = static_cast<unsigned>(k_c1 - k_c0) - (st.ph[0] + st.ph[1] + st.ph[2] + st.ph[3] + st.ph[4] + st.ph[5] + st.ph[6]);   // before the main loop
+            r[11] = static_cast<unsigned>(k_c2 - k_c1);         // after the main loop: masked blocks and epilogue
+        }
+    }
+#endif
 #endif
 }
 
@@ -802,9 +866,13 @@ extern "C" int ifa_debug_fwd(const signed char *Q_i8, const signed char *K_i8, c
 }
 
 #if IFA_STAMP
+extern "C" int ifa_debug_read_wave_records(unsigned *out, long waves) {
+    if (waves > STAMP_WAVES) return IFA_ERR_SHAPE;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wave_rec), waves * 48) == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+}
 extern "C" int ifa_debug_read_stamps(unsigned long long *out16, int reset) {
-    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_stamp), 128) != hipSuccess) return IFA_ERR_HIP;
-    if (reset) { unsigned long long z[16] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 128) != hipSuccess) return IFA_ERR_HIP; }
+    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_stamp), 256) != hipSuccess) return IFA_ERR_HIP;
+    if (reset) { unsigned long long z[32] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 256) != hipSuccess) return IFA_ERR_HIP; }
     return IFA_OK;
 }
 #endif

@@ -114,7 +114,7 @@ __device__ __forceinline__ float uniform(float x) {
 // ever read by the next MFMA of the chain (same registers as its accumulator, which may follow back to back).
 __device__ __forceinline__ v16i mfma_i8_start(const v4i &a, const v4i &b) {
     v16i d;
-    asm("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(d) : "v"(a), "v"(b));
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(d) : "v"(a), "v"(b));
     return d;
 }
 

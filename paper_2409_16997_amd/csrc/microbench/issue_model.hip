@@ -45,10 +45,11 @@ struct WaveRec {
 };
 constexpr int MAX_WAVES = 256 * 16 * 4;
 
-enum { FMA1 = 0, FMA3, ADDLIT, MUL2, MAX3, CVTPK, EXP, FMAC, SADU8, NOP_OP };
+enum { FMA1 = 0, FMA3, ADDLIT, MUL2, MAX3, CVTPK, EXP, FMAC, SADU8, NOP_OP, SDWAADD, DOT4, SUBINL, MIN3, PKNORM, PERM, MAX2, CVTI, PKRTZ, PKADD16 };
 static const char *OP_NAME[] = {"v_fma_f32 x,x,0.5,0.5", "v_fma_f32 x,x,y,z", "v_add_f32 x,lit,x", "v_mul_f32 x,x,y",
                                 "v_max3_f32 x,x,y,z",    "v_cvt_pk_u8_f32 x,y,1,x", "v_exp_f32 x,x", "v_fmac_f32 x,y,z",
-                                "v_sad_u8 x,x,0,y", "-"};
+                                "v_sad_u8 x,x,0,y", "-", "v_add_f32_sdwa x.b1,y,z", "v_dot4_u32_u8 x,y,z,x", "v_sub_f32 x,inv2pi,x", "v_min3_f32 x,x,y,z", "v_cvt_pknorm_u16_f32 x,x,y", "v_perm_b32 x,x,y,z", "v_max_f32 x,x,y", "v_cvt_f32_i32 x,x",
+                                "v_cvt_pkrtz_f16_f32 x,x,y", "v_pk_add_u16 x,x,y"};
 
 #if defined(__HIP_DEVICE_COMPILE__)
 template <int OP> __device__ __forceinline__ void vop(float &x, float y, float z) {
@@ -61,6 +62,16 @@ template <int OP> __device__ __forceinline__ void vop(float &x, float y, float z
     else if constexpr (OP == EXP) asm volatile("v_exp_f32 %0, %0" : "+v"(x));
     else if constexpr (OP == FMAC) asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(x) : "v"(y), "v"(z));
     else if constexpr (OP == SADU8) asm volatile("v_sad_u8 %0, %0, 0, %1" : "+v"(x) : "v"(y));
+    else if constexpr (OP == SDWAADD) asm volatile("v_add_f32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(x) : "v"(y), "v"(z));
+    else if constexpr (OP == DOT4) asm volatile("v_dot4_u32_u8 %0, %1, %2, %0" : "+v"(x) : "v"(y), "v"(z));
+    else if constexpr (OP == SUBINL) asm volatile("v_sub_f32 %0, 0.15915494, %0" : "+v"(x));
+    else if constexpr (OP == PKNORM) asm volatile("v_cvt_pknorm_u16_f32 %0, %0, %1" : "+v"(x) : "v"(y));
+    else if constexpr (OP == PERM) asm volatile("v_perm_b32 %0, %0, %1, %2" : "+v"(x) : "v"(y), "v"(z));
+    else if constexpr (OP == MAX2) asm volatile("v_max_f32 %0, %0, %1" : "+v"(x) : "v"(y));
+    else if constexpr (OP == CVTI) asm volatile("v_cvt_f32_i32 %0, %0" : "+v"(x));
+    else if constexpr (OP == PKRTZ) asm volatile("v_cvt_pkrtz_f16_f32 %0, %0, %1" : "+v"(x) : "v"(y));
+    else if constexpr (OP == PKADD16) asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(x) : "v"(y));
+    else if constexpr (OP == MIN3) asm volatile("v_min3_f32 %0, %0, %1, %2" : "+v"(x) : "v"(y), "v"(z));
 }
 __device__ __forceinline__ void mfma(v16i &c, const v4i &a, const v4i &b) {
     asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
@@ -381,7 +392,7 @@ __global__ __launch_bounds__(256 * W) void layers_kernel(LayerIters li, WaveRec 
 //   M2 only; 4: in M1 only; 5: as 1 with priority 1 instead of 3
 //   LDS_KB: static LDS per workgroup: 96 admits one workgroup per CU, 64 two (then W = 1 and the grid has 2 per CU:
 //   the two wavefronts of a SIMD come from different workgroups, as in the attention kernel)
-template <int STRUCT, int PRIO, int W, int LDS_KB = 96>
+template <int STRUCT, int PRIO, int W, int LDS_KB = 96, int STAG = 0>
 __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec, float *sink, float seed) {
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ float keep_out[LDS_KB * 256];
@@ -481,6 +492,7 @@ __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec,
                     for (int i = 0; i < 8; ++i) vop<MAX3>(r.x[16 + i], r.y, r.z);
                 }
             }
+            if (STAG == 3 && (threadIdx.x >> 8) == 1) __builtin_amdgcn_s_barrier();   // half a block apart
             // V2 / M2
             if (STRUCT == 5) {
                 p_tile(0, 2);
@@ -549,6 +561,10 @@ __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec,
                 }
                 prio_v();
             }
+            // STAG 1: the two wavefronts of a SIMD (w and w + 4) meet one workgroup barrier per block at DIFFERENT points of
+            // their program -- wavefronts 4-7 in front of V3, wavefronts 0-3 behind it -- which holds them one section apart;
+            // STAG 2: same barrier point for all (behind V3): held in the same section
+            if (STAG == 1 && (threadIdx.x >> 8) == 1) __builtin_amdgcn_s_barrier();
             // V3
             if (STRUCT != 3) {
 #pragma unroll
@@ -559,6 +575,7 @@ __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec,
                     for (int i = 0; i < 16; ++i) vop<FMA3>(r.x[16 + (i & 7)], r.x[i], r.z);
                 }
             }
+            if (((STAG == 1 || STAG == 3) && (threadIdx.x >> 8) == 0) || STAG == 2) __builtin_amdgcn_s_barrier();
         }
     }
     const Stamp t1 = stamp();
@@ -650,7 +667,7 @@ int main(int argc, char **argv) {
     if (want("solo")) {
         printf("\n== solo: 32 instructions of one kind per unit (cycles per unit / 32 = cycles per instruction per SIMD)\n");
 #define SOLO(OP) MIX(0, 0, OP, 32, 0, 1, 1) MIX(0, 0, OP, 32, 0, 1, 2) MIX(0, 0, OP, 32, 0, 1, 4)
-        SOLO(FMA1) SOLO(FMA3) SOLO(ADDLIT) SOLO(MUL2) SOLO(MAX3) SOLO(CVTPK) SOLO(FMAC) SOLO(SADU8)
+        SOLO(FMA1) SOLO(FMA3) SOLO(ADDLIT) SOLO(MUL2) SOLO(MAX3) SOLO(CVTPK) SOLO(FMAC) SOLO(SADU8) SOLO(SDWAADD) SOLO(DOT4) SOLO(SUBINL) SOLO(PKNORM) SOLO(PERM) SOLO(MAX2) SOLO(CVTI) SOLO(PKRTZ) SOLO(PKADD16)
         MIX(0, 0, NOP_OP, 0, 16, 1, 1) MIX(0, 0, NOP_OP, 0, 16, 1, 2) MIX(0, 0, NOP_OP, 0, 16, 1, 4)
         printf("   (last three lines: 16 v_exp_f32 per unit)\n");
     }
@@ -787,6 +804,17 @@ int main(int argc, char **argv) {
         PHASE(2, 3, 2) PHASE(2, 4, 2) PHASE(2, 5, 2)
         PHASE(4, 0, 2) PHASE(4, 1, 2) PHASE(4, 3, 2)
         PHASE(5, 0, 2) PHASE(5, 1, 2) PHASE(5, 3, 2)
+        printf("   one 8-wavefront workgroup, one barrier per block: same point for all wavefronts / wavefronts 4-7 one section ahead of it (in front of V3) / half a block ahead (in front of M2):\n");
+#define PHASESTAG(ST, PR, SG)                                                                                                    \
+    {                                                                                                                           \
+        const Result r = run([&] { hipLaunchKernelGGL((phase_kernel<ST, PR, 2, 96, SG>), CU, 512, 0, 0, bit, g_rec, g_sink, 0.5f); }, CU * 8); \
+        printf("   stagger %d: ", SG);                                                                                         \
+        phase_line(ST, PR, 2, r);                                                                                               \
+    }
+        PHASESTAG(1, 0, 2) PHASESTAG(1, 0, 1) PHASESTAG(1, 0, 3)
+        PHASESTAG(2, 0, 2) PHASESTAG(2, 0, 1) PHASESTAG(2, 0, 3)
+        PHASESTAG(2, 3, 2) PHASESTAG(2, 3, 1) PHASESTAG(2, 3, 3)
+        PHASESTAG(1, 3, 1) PHASESTAG(1, 1, 1) PHASESTAG(2, 1, 1)
         printf("   two 4-wavefront workgroups per CU (64 KB of LDS each) instead of one 8-wavefront workgroup:\n");
 #define PHASE2WG(ST, PR)                                                                                                        \
     {                                                                                                                           \
