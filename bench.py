@@ -104,15 +104,16 @@ def main():
 
     def step(i=None):
         if not args.attn_only or "Qq" not in state:
-            Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
-            Kq, sK = ifa.quantize_tokenwise(K)
-            state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK)
-            if vblock:
-                Vq, sV = ifa.quantize_blockwise(V, ifa.block_cols(w.d, w.causal))
-                state.update(Vq=Vq, sV=sV)
-            elif not half:
-                Vq, sV = ifa.quantize_headwise(V)
-                state.update(Vq=Vq, sV=sV)
+            if not half and not vblock:            # Q, K token-level and V tensor-level: the fused preparation call
+                Qq, Kq, Vq, sQ, sK, sV = ifa.quantize_qkv(Q, K, V, s_Q_mul=fold, out=state.get("bufs"))
+                state.update(Qq=Qq, Kq=Kq, Vq=Vq, sQ=sQ, sK=sK, sV=sV, bufs=(Qq, Kq, Vq, sQ, sK, sV))
+            else:
+                Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
+                Kq, sK = ifa.quantize_tokenwise(K)
+                state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK)
+                if vblock:
+                    Vq, sV = ifa.quantize_blockwise(V, ifa.block_cols(w.d, w.causal))
+                    state.update(Vq=Vq, sV=sV)
         s = state
         if i is not None:
             ev[i][0].record()

@@ -43,7 +43,7 @@ int ifa_set_stream(void *hip_stream);
 
 /*
  * Token-level symmetric INT8 quantization of Q and K (Section 3.2: S_Q = rowmax|Q| / R,
- * S_K = rowmax|K| / R, "linear symmetric quantization").
+ * S_K = rowmax|K| / R; symmetric, no zero point).
  *   X       [rows, d] real activations of dtype x_dtype (ifa_dtype), rows = B*H*N
  *   Xq      [rows, d] int8 out:  q = clamp(rint(x * (127 / a)), -127, 127), a = max_k |x[r,k]|
  *   scale   [rows] fp32 out:     a / 127  (fp32 divide); an all-zero row gets scale 1, q = 0
@@ -85,6 +85,25 @@ int quantize_tokenwise_hadamard(const void *X, int x_dtype, long rows, int d,
 int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d,
                       signed char *Xq, float *scale, int global_scale);
 
+/* Same, on an explicit stream. */
+int quantize_headwise_ex(const void *X, int x_dtype, long heads, long N, int d,
+                         signed char *Xq, float *scale, int global_scale, void *hip_stream);
+
+/*
+ * The whole input preparation of Section 3.2 for one attention call, in four launches instead of the six the
+ * three separate calls take: token-level quantization of Q and K in ONE launch (which also clears the slots the
+ * absmax pass of V accumulates into), then the two passes of V and the conversion of its absmax to scales.
+ *   Q, K, V          [heads, N, d] real activations of dtype x_dtype, heads = B*H
+ *   Q_i8, K_i8, V_i8 [heads, N, d] int8 out;  s_Q, s_K [heads, N] and s_V [heads] fp32 out
+ *   s_Q_mul          multiplier folded into the stored s_Q (1/sqrt(d) for the usual softmax scale; 1 for none)
+ * Results are bit-identical to quantize_tokenwise_ex(Q, ..., s_Q_mul), quantize_tokenwise_ex(K, ..., 1) and
+ * quantize_headwise(V, ..., global_scale = 0).  Argument rules of those calls apply (d in {32 ... 512}, N*d a
+ * multiple of 8, alignment); nothing is enqueued on an error.
+ */
+int quantize_qkv(const void *Q, const void *K, const void *V, int x_dtype, long heads, long N, int d,
+                 signed char *Q_i8, signed char *K_i8, signed char *V_i8, float *s_Q, float *s_K, float *s_V,
+                 float s_Q_mul, void *hip_stream);
+
 /*
  * Algorithm 1 (INT-FlashAttention forward), lines 4-18, for every (b, h) head:
  *   S = diag(s_Q) (Q K^T) diag(s_K)          int8 x int8 -> int32 on MFMA, then fp32 scales
@@ -125,7 +144,7 @@ int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, co
 
 /*
  * Per-block quantization of V -- the scheme the paper names as its next step (Section 3.2, footnote;
- * Section 5: "we will use per-block quantization to optimize the implementation of the V matrix").
+ * Section 5, which names per-block quantization of V as the next step).
  * One scale per (head, block of block_keys consecutive keys) = per V_j of Algorithm 1:
  *   X [heads, N, d] -> Xq [heads, N, d] int8 (same rounding rule as above),
  *   scale [heads, ceil(N / block_keys)] fp32 = max|V_j| / 127 (1 for an all-zero block).
@@ -155,7 +174,7 @@ int int_flash_attn_fwd_vblock_rect(const signed char *Q_i8, const signed char *K
                                    void *hip_stream);
 
 /*
- * Half-INT8 variant (Section 4: "INT8-format Q and K matrices and FP16-format V matrix"): lines 9-10 of
+ * Half-INT8 variant (Section 4: Q and K in INT8, V kept in FP16): lines 9-10 of
  * Algorithm 1 as above, then the softmax weights stay real and are rounded to FP16 for the second GEMM:
  *   P~ = fp16(exp(S - m))  (nearest even, no factor R);   l = e^{m_old - m} l + rowsum(P~)  (the rounded weights, fp32)
  *   O  = e^{m_old - m} O + P~ V_j  (fp16 x fp16 products, fp32 accumulation);   O = diag(l)^-1 O

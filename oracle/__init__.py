@@ -14,6 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "intfa_oracle.c")
 _LIB = os.path.join(_HERE, "_intfa_oracle.so")
+_LIB_SANITIZED = os.path.join(_HERE, "_intfa_oracle_sanitized.so")
 
 # No fast-math, no contraction: every fp32 operation in the C file rounds once, as written.
 _CFLAGS = ["-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
@@ -27,13 +28,23 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (any report aborts), for the test that runs
+    the pins against it in a child process (the sanitizer runtime has to be preloaded into that process)."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-Wall", "-Wextra",
+                           _SRC, "-o", _LIB_SANITIZED, "-lm"])
+    return _LIB_SANITIZED
+
+
 _lib = None
 
 
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        # INTFA_ORACLE_LIB: a prebuilt library to load instead (the sanitized build, in the child process of its test)
+        lib = ctypes.CDLL(os.environ.get("INTFA_ORACLE_LIB") or build())
         vp, i64, i32, f64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_double
         lib.orc_num_threads.restype = ctypes.c_int
         lib.orc_quantize_rows.argtypes = [vp, i64, i64, vp, vp]

@@ -37,7 +37,7 @@ int orc_num_threads(void)
 #endif
 }
 
-/* Section 3.2 ("linear symmetric quantization", S = rowmax|X| / R).
+/* Section 3.2 (symmetric quantization without a zero point, S = rowmax|X| / R).
  * One scale per row of a [rows, cols] matrix: cols = d gives the token-level scheme of
  * Q and K; rows = heads, cols = N*d gives the tensor-level scheme of V.
  *   a = max|x|, s = a / 127, q = clamp(rint(x * (127 / a)), -127, 127); a == 0 -> s = 1, q = 0.
@@ -70,7 +70,7 @@ void orc_quantize_rows(const float *X, int64_t rows, int64_t cols, int8_t *q, fl
 }
 
 /* Walsh-Hadamard transform of every row (Sylvester order, unnormalized: H_d H_d = d I), the rotation the paper
- * names as future work (Section 5: "combine ... with Hadamard transformations").  Applied to the rows of both
+ * names as future work (Section 5, the combination with Hadamard transformations).  Applied to the rows of both
  * Q and K it leaves Q K^T unchanged up to the factor d, and spreads outlier channels over all channels before
  * the token-level quantization.  The butterflies run in fp32 in the textbook order h = 1, 2, 4, ...:
  * (x[i], x[i+h]) <- (x[i] + x[i+h], x[i] - x[i+h]) for every i with bit h clear.  cols must be a power of two. */

@@ -18,6 +18,8 @@ SIGNATURES = {
     "quantize_tokenwise_ex": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
     "quantize_tokenwise_hadamard": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
+    "quantize_headwise_ex": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i, _vp]),
+    "quantize_qkv": (_i, [_vp, _vp, _vp, _i, _l, _l, _i, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
@@ -109,11 +111,29 @@ def quantize_headwise(X, global_scale=False):
     heads = X.numel() // (N * d)
     Xq = torch.empty(X.shape, dtype=torch.int8, device=X.device)
     scale = torch.empty(X.shape[:-2], dtype=torch.float32, device=X.device)
-    L = lib()
-    L.ifa_set_stream(_stream())
-    _check(L.quantize_headwise(_dev(X), _dtype_enum(X), heads, N, d, _dev(Xq), _dev(scale), int(bool(global_scale))),
-           "quantize_headwise")
+    _check(lib().quantize_headwise_ex(_dev(X), _dtype_enum(X), heads, N, d, _dev(Xq), _dev(scale), int(bool(global_scale)),
+                                      _stream()), "quantize_headwise_ex")
     return Xq, scale
+
+
+def quantize_qkv(Q, K, V, s_Q_mul=1.0, out=None):
+    """The input preparation of one attention call in four launches: Q, K token-level, V tensor-level.
+    Q, K, V [B, H, N, d] -> (Q_i8, K_i8, V_i8, s_Q [B, H, N] (times s_Q_mul), s_K [B, H, N], s_V [B, H]);
+    out: optional tuple of those six tensors to write into."""
+    import torch
+    assert Q.shape == K.shape == V.shape and Q.dtype == K.dtype == V.dtype
+    N, d = Q.shape[-2], Q.shape[-1]
+    heads = Q.numel() // (N * d)
+    if out is None:
+        q8, k8, v8 = (torch.empty(Q.shape, dtype=torch.int8, device=Q.device) for _ in range(3))
+        sq, sk = (torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device) for _ in range(2))
+        sv = torch.empty(Q.shape[:-2], dtype=torch.float32, device=Q.device)
+    else:
+        q8, k8, v8, sq, sk, sv = out
+    _check(lib().quantize_qkv(_dev(Q), _dev(K), _dev(V), _dtype_enum(Q), heads, N, d, _dev(q8, torch.int8), _dev(k8, torch.int8),
+                              _dev(v8, torch.int8), _dev(sq, torch.float32), _dev(sk, torch.float32), _dev(sv, torch.float32),
+                              float(s_Q_mul), _stream()), "quantize_qkv")
+    return q8, k8, v8, sq, sk, sv
 
 
 def quantize_blockwise(X, block_keys):

@@ -151,9 +151,9 @@ template <> struct Pack4<__half> {
     }
 };
 template <> struct Pack4<__hip_bfloat16> {
-    static __device__ __forceinline__ uint32_t rne(float x) {   // fp32 -> bf16 bits, round half to even
+    static __device__ __forceinline__ uint32_t rne(float x) {   // fp32 -> bf16 bits, round half to even; NaN stays NaN
         uint32_t u = __float_as_uint(x);
-        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+        return (x != x) ? 0x7fc0u : (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     }
     static __device__ __forceinline__ uint2 pack(float a, float b, float c, float d) {
         uint2 w;

@@ -120,24 +120,35 @@ template <int LPR> __device__ __forceinline__ void hadamard_row(float (&x)[8], i
 }
 
 // ---- token-level: one row = LPR lanes ---------------------------------------------------------
+// One launch serves up to two tensors of the same shape (blockIdx.y picks one: Q and K of a step), and can clear an
+// array of words on the side (the absmax slots the tensor-level quantizer of V accumulates into afterwards).
+struct TokenJob {
+    const void *X;
+    int8_t *Xq;
+    float *scale;
+    float scale_mul;
+};
 template <typename T, int LPR, bool HADAMARD>
-__global__ __launch_bounds__(256) void quantize_tokenwise_kernel(const void *__restrict__ X, long rows,
-                                                                 int8_t *__restrict__ Xq,
-                                                                 float *__restrict__ scale, float scale_mul) {
+__global__ __launch_bounds__(256) void quantize_tokenwise_kernel(TokenJob j0, TokenJob j1, long rows,
+                                                                 unsigned *__restrict__ clear, long clear_words) {
     constexpr int D = LPR * 8;
     constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    const TokenJob job = blockIdx.y == 0 ? j0 : j1;
     const int sub = threadIdx.x % LPR;
+    if (blockIdx.y == 0)
+        for (long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x; i < clear_words; i += static_cast<long>(gridDim.x) * 256)
+            clear[i] = 0u;
     const long row_stride = static_cast<long>(gridDim.x) * ROWS_PER_BLOCK;
     for (long row = static_cast<long>(blockIdx.x) * ROWS_PER_BLOCK + threadIdx.x / LPR; row < rows;
          row += row_stride) {
         float x[8];
         const long idx = row * D + sub * 8;
-        Load8<T>::get(X, idx, x);
+        Load8<T>::get(job.X, idx, x);
         if (HADAMARD) hadamard_row<LPR>(x, sub);
         const float a = group_max<LPR>(absmax8(x));
         const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
-        *reinterpret_cast<uint2 *>(Xq + idx) = quant8(x, inv);
-        if (sub == 0) scale[row] = ((a == 0.0f) ? 1.0f : a / 127.0f) * scale_mul;
+        *reinterpret_cast<uint2 *>(job.Xq + idx) = quant8(x, inv);
+        if (sub == 0) job.scale[row] = ((a == 0.0f) ? 1.0f : a / 127.0f) * job.scale_mul;
     }
 }
 
@@ -234,18 +245,20 @@ __global__ void head_scale_finalize_kernel(float *scale, long heads, int global_
 }
 
 template <typename T, bool HADAMARD>
-int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, float scale_mul, hipStream_t st) {
+int launch_tokenwise(const TokenJob &j0, const TokenJob &j1, int jobs, long rows, int d, unsigned *clear, long clear_words,
+                     hipStream_t st) {
     const int lpr = d / 8;
     const long rows_per_block = 256 / lpr;
     long blocks = (rows + rows_per_block - 1) / rows_per_block;
-    if (blocks > 256L * 64) blocks = 256L * 64;          // grid-stride beyond 64 blocks per CU (4 to 64 measured alike)
-    const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+    const long cap = 256L * 64 / jobs;                   // grid-stride beyond 64 blocks per CU (4 to 64 measured alike)
+    if (blocks > cap) blocks = cap;
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(jobs)), block(256);
     switch (lpr) {
-    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
-    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64, HADAMARD>), grid, block, 0, st, X, rows, Xq, scale, scale_mul); break;
+    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
+    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
+    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
+    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
+    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
     default: return IFA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
@@ -253,9 +266,10 @@ int launch_tokenwise(const void *X, long rows, int d, int8_t *Xq, float *scale, 
 
 template <typename T>
 int launch_headwise(const void *X, long heads, long per_head, int8_t *Xq, float *scale, int global_scale,
-                    hipStream_t st) {
+                    hipStream_t st, bool slots_cleared = false) {
     unsigned *bits = reinterpret_cast<unsigned *>(scale);
-    hipLaunchKernelGGL(zero_words_kernel, dim3(static_cast<unsigned>((heads + 255) / 256)), dim3(256), 0, st, bits, heads);
+    if (!slots_cleared)
+        hipLaunchKernelGGL(zero_words_kernel, dim3(static_cast<unsigned>((heads + 255) / 256)), dim3(256), 0, st, bits, heads);
     long bx = (per_head / 8 + 255) / 256;
     // About 4 workgroups per CU in total: measured on MI355X (c3's V, 134 MB) the two passes take 92 us with 1 per
     // CU, 64 with 2, 57 with 4 or 8, 64 with 16, 72 with 32 -- more workgroups only add atomics on the head's slot.
@@ -272,21 +286,52 @@ int launch_headwise(const void *X, long heads, long per_head, int8_t *Xq, float 
 }  // namespace
 
 namespace {
-template <bool HADAMARD>
-int tokenwise_entry(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale, float scale_mul,
-                    void *hip_stream) {
+int tokenwise_args(const void *X, int x_dtype, long rows, int d, const signed char *Xq, const float *scale, float scale_mul) {
     if (!X || !Xq || !scale) return IFA_ERR_NULL;
     if (rows <= 0 || d <= 0 || rows > (1L << 40) / d) return IFA_ERR_SHAPE;
     if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
     if (d != 32 && d != 64 && d != 128 && d != 256 && d != 512) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
     if (!(scale_mul > 0.0f) || scale_mul > 3.0e38f) return IFA_ERR_SHAPE;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    int8_t *q = reinterpret_cast<int8_t *>(Xq);
+    return IFA_OK;
+}
+
+template <bool HADAMARD>
+int tokenwise_launch(const TokenJob &j0, const TokenJob &j1, int jobs, int x_dtype, long rows, int d, unsigned *clear,
+                     long clear_words, hipStream_t st) {
     switch (x_dtype) {
-    case IFA_F32: return launch_tokenwise<float, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
-    case IFA_F16: return launch_tokenwise<__half, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
-    default: return launch_tokenwise<__hip_bfloat16, HADAMARD>(X, rows, d, q, scale, scale_mul, st);
+    case IFA_F32: return launch_tokenwise<float, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
+    case IFA_F16: return launch_tokenwise<__half, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
+    default: return launch_tokenwise<__hip_bfloat16, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
+    }
+}
+
+template <bool HADAMARD>
+int tokenwise_entry(const void *X, int x_dtype, long rows, int d, signed char *Xq, float *scale, float scale_mul,
+                    void *hip_stream) {
+    const int rc = tokenwise_args(X, x_dtype, rows, d, Xq, scale, scale_mul);
+    if (rc != IFA_OK) return rc;
+    const TokenJob job = {X, reinterpret_cast<int8_t *>(Xq), scale, scale_mul};
+    return tokenwise_launch<HADAMARD>(job, job, 1, x_dtype, rows, d, nullptr, 0, static_cast<hipStream_t>(hip_stream));
+}
+
+int headwise_args(const void *X, int x_dtype, long heads, long N, int d, const signed char *Xq, const float *scale) {
+    if (!X || !Xq || !scale) return IFA_ERR_NULL;
+    if (heads <= 0 || N <= 0 || d <= 0 || heads > 65535 || N > (1L << 40) / d / heads) return IFA_ERR_SHAPE;
+    if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
+    if ((N * d) % 8 != 0) return IFA_ERR_UNSUPPORTED;
+    if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
+    return IFA_OK;
+}
+
+int headwise_launch(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq, float *scale, int global_scale,
+                    hipStream_t st, bool slots_cleared) {
+    int8_t *q = reinterpret_cast<int8_t *>(Xq);
+    const int g = global_scale ? 1 : 0;
+    switch (x_dtype) {
+    case IFA_F32: return launch_headwise<float>(X, heads, N * d, q, scale, g, st, slots_cleared);
+    case IFA_F16: return launch_headwise<__half>(X, heads, N * d, q, scale, g, st, slots_cleared);
+    default: return launch_headwise<__hip_bfloat16>(X, heads, N * d, q, scale, g, st, slots_cleared);
     }
 }
 }  // namespace
@@ -325,20 +370,29 @@ extern "C" int quantize_blockwise(const void *X, int x_dtype, long heads, long N
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
+extern "C" int quantize_headwise_ex(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq,
+                                    float *scale, int global_scale, void *hip_stream) {
+    const int rc = headwise_args(X, x_dtype, heads, N, d, Xq, scale);
+    if (rc != IFA_OK) return rc;
+    return headwise_launch(X, x_dtype, heads, N, d, Xq, scale, global_scale, static_cast<hipStream_t>(hip_stream), false);
+}
+
 extern "C" int quantize_headwise(const void *X, int x_dtype, long heads, long N, int d, signed char *Xq,
                                  float *scale, int global_scale) {
-    if (!X || !Xq || !scale) return IFA_ERR_NULL;
-    if (heads <= 0 || N <= 0 || d <= 0 || heads > 65535 || N > (1L << 40) / d / heads) return IFA_ERR_SHAPE;
-    if (x_dtype < IFA_F32 || x_dtype > IFA_BF16) return IFA_ERR_DTYPE;
-    const long per_head = N * d;
-    if (per_head % 8 != 0) return IFA_ERR_UNSUPPORTED;
-    if (!ifa_aligned16(X) || !ifa_aligned16(Xq) || (reinterpret_cast<uintptr_t>(scale) & 3)) return IFA_ERR_UNSUPPORTED;
-    hipStream_t st = ifa_current_stream();
-    int8_t *q = reinterpret_cast<int8_t *>(Xq);
-    const int g = global_scale ? 1 : 0;
-    switch (x_dtype) {
-    case IFA_F32: return launch_headwise<float>(X, heads, per_head, q, scale, g, st);
-    case IFA_F16: return launch_headwise<__half>(X, heads, per_head, q, scale, g, st);
-    default: return launch_headwise<__hip_bfloat16>(X, heads, per_head, q, scale, g, st);
-    }
+    return quantize_headwise_ex(X, x_dtype, heads, N, d, Xq, scale, global_scale, ifa_current_stream());
+}
+
+extern "C" int quantize_qkv(const void *Q, const void *K, const void *V, int x_dtype, long heads, long N, int d,
+                            signed char *Q_i8, signed char *K_i8, signed char *V_i8, float *s_Q, float *s_K, float *s_V,
+                            float s_Q_mul, void *hip_stream) {
+    int rc = headwise_args(V, x_dtype, heads, N, d, V_i8, s_V);             // bounds heads * N * d first
+    if (rc == IFA_OK) rc = tokenwise_args(Q, x_dtype, heads * N, d, Q_i8, s_Q, s_Q_mul);
+    if (rc == IFA_OK) rc = tokenwise_args(K, x_dtype, heads * N, d, K_i8, s_K, 1.0f);
+    if (rc != IFA_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const TokenJob jq = {Q, reinterpret_cast<int8_t *>(Q_i8), s_Q, s_Q_mul}, jk = {K, reinterpret_cast<int8_t *>(K_i8), s_K, 1.0f};
+    // one launch for Q and K, which also clears the slots the absmax pass of V accumulates into
+    rc = tokenwise_launch<false>(jq, jk, 2, x_dtype, heads * N, d, reinterpret_cast<unsigned *>(s_V), heads, st);
+    if (rc != IFA_OK) return rc;
+    return headwise_launch(V, x_dtype, heads, N, d, V_i8, s_V, 0, st, true);
 }

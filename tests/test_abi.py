@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_headwise_ex", "quantize_qkv", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 

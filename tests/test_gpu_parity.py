@@ -144,6 +144,27 @@ def test_quantize_workload_heads_bit_exact(ifa):
             assert np.array_equal(q.cpu().numpy(), rq) and np.array_equal(s.cpu().numpy(), rs)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("B,H,N,d", [(2, 3, 384, 64), (1, 5, 200, 128), (1, 2, 37, 32)])
+def test_quantize_qkv_equals_the_three_separate_calls(ifa, dtype, B, H, N, d):
+    # the fused preparation (one launch for Q and K, which also clears V's absmax slots) against the separate entry
+    # points, bit for bit, twice in a row into the same buffers (the second call must not see the first one's slots)
+    g = torch.Generator(device="cuda").manual_seed(B * 1000 + N + d)
+    Q, K, V = (torch.randn((B, H, N, d), generator=g, device="cuda", dtype=torch.float32).to(dtype) for _ in range(3))
+    V[0, 0] = 0                                            # an all-zero head: scale 1, codes 0
+    fold = 1.0 / math.sqrt(d)
+    rq, rsq = ifa.quantize_tokenwise(Q, scale_mul=fold)
+    rk, rsk = ifa.quantize_tokenwise(K)
+    rv, rsv = ifa.quantize_headwise(V)
+    out = ifa.quantize_qkv(Q, K, V, s_Q_mul=fold)
+    for _ in range(2):
+        got = ifa.quantize_qkv(Q, K, V * 0.5 if _ == 0 else V, s_Q_mul=fold, out=out)   # first pass leaves other absmax values behind
+    torch.cuda.synchronize()
+    for a, b in zip(got, (rq, rk, rv, rsq, rsk, rsv)):
+        assert torch.equal(a, b)
+    assert float(rsv[0, 0]) == 1.0 and not bool(rv[0, 0].any())
+
+
 # ------------------------------------------------------------------ int32 accumulators: bit-exact
 
 def _oracle_block_pv(P, V, Bc):
