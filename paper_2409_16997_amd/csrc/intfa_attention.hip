@@ -724,6 +724,212 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #endif
 }
 
+// ---- few queries, many keys (a decode step, a short chunk of a prefill) ---------------------------------------
+// With at most a few dozen queries per head the kernel above would keep three of its four wavefronts idle and one
+// workgroup per head cannot fill the chip; what limits such a call is how fast K and V stream in.  Here the four
+// wavefronts of a workgroup share ONE group of 32 queries and split each 128-key block instead:
+//     wavefront w computes S^T for key tile w (32 keys; 4 MFMAs), scales it, takes its minimum / maximum;
+//     the four per-query extrema meet in LDS (first barrier of the block): everyone knows m of line 10 for the whole block;
+//     wavefront w computes the 16 P bytes per lane of its key tile and leaves them in LDS (second barrier);
+//     wavefront w then computes the d tile w (32 of the d columns) of O^T = V^T P^T over ALL 128 keys (4 MFMAs,
+//     P operands of the four key tiles from LDS) and folds it into its 16 registers of the running output.
+// Every number is computed by the same instruction sequence on the same operands as in the kernel above (the
+// integer sums are exact, the extremum is order-independent, the row sum l is taken over the same P dwords), so
+// the output is bit-identical to the corresponding rows of a square call: still Algorithm 1 at B_c = 128.
+// K and V come in through a ring of NSTAGE blocks (one workgroup per CU: there are few workgroups anyway), filled
+// three blocks ahead so that enough bytes are in flight to cover the HBM latency; the wait for a block is a
+// counted s_waitcnt (every wavefront issues the same number of copy instructions per block) in front of the second
+// barrier of the block before, which thereby also publishes the staged block; the first barrier releases the
+// stage of the block before for refilling.
+constexpr int NARROW_BR = 32;      // queries per workgroup
+constexpr int NSTAGE = 4;
+
+template <int D> struct SmemNarrow {
+    alignas(4096) int8_t k[NSTAGE][BC * D];
+    alignas(4096) int8_t v[NSTAGE][BC * D];
+    alignas(512) float sk[NSTAGE][BC];
+    alignas(16) float ext[4][32];          // per key tile and query: the tile's extremum of a (line 10)
+    alignas(16) v4i p[4][64];              // per key tile and lane: the 16 P bytes of that lane (line 11)
+};
+static_assert(sizeof(SmemNarrow<128>) <= 160 * 1024 && offsetof(SmemNarrow<64>, v) % 4096 == 0, "LDS budget and tile bases");
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int D, bool CAUSAL, typename OutT>
+__global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
+    const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
+    const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
+    int heads, int Nq, int Nk, OutT *__restrict__ O) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __shared__ SmemNarrow<D> sm;
+    constexpr int KS = D / 32;
+    constexpr int PER_BLOCK = 2 * KS + 1;                        // copy instructions per wavefront and block
+
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T_c = (Nk + BC - 1) / BC;
+    const int qgroups = (Nq + NARROW_BR - 1) / NARROW_BR;
+    const int shift = CAUSAL ? Nk - Nq : 0;
+    // all query groups of a head on one XCD (workgroups go round-robin over the 8 XCDs by linear id)
+    int head, qg;
+    if ((heads & 7) == 0) { const int s_ = blockIdx.x >> 3; head = (s_ / qgroups) * 8 + (blockIdx.x & 7); qg = s_ % qgroups; }
+    else { head = blockIdx.x / qgroups; qg = blockIdx.x % qgroups; }
+    const int first_q = qg * NARROW_BR;
+    const int q_head = first_q + r;
+    const long qrow = static_cast<long>(head) * Nq + min(q_head, Nq - 1);   // rows past Nq: a clamped copy, never stored
+
+    const int8_t *Kh = K + static_cast<long>(head) * Nk * D;
+    const int8_t *Vh = V + static_cast<long>(head) * Nk * D;
+    const float *sKh = sK + static_cast<long>(head) * Nk;
+    const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
+    const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
+    const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0]);
+    const int nblocks = CAUSAL ? min(Nk - 1, min(first_q + NARROW_BR, Nq) - 1 + shift) / BC + 1 : T_c;
+
+    const BufRsrc rK = make_rsrc(Kh, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rV = make_rsrc(Vh, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rSK = make_rsrc(sKh, static_cast<unsigned>(Nk) * 4);
+    const LaneOffsets<D> lo(lane, wave);
+
+    // line 8 for block jb into stage jb % NSTAGE; a block past the last one is requested nowhere (no data moves), so
+    // that every block costs every wavefront PER_BLOCK copy instructions and the counted wait below stays valid
+    auto stage_block = [&](int jb) {
+        const int st = jb % NSTAGE;
+        const bool real = jb < nblocks;
+        const Prefetch pf = {rK, rV, rSK, real ? jb * BC * D : NOWHERE, real ? jb * BC * 4 : NOWHERE,
+                             kbuf + st * BC * D, vbuf + st * BC * D, skbuf + st * BC * 4};
+#pragma unroll
+        for (int i = 0; i < KS; ++i) { prefetch_k_piece<D>(pf, lo, wave, i); prefetch_v_piece<D>(pf, lo, wave, i); }
+        lds_copy4(pf.sk, pf.lsk + 256 * (wave & 1), 4 * lane + 256 * (wave & 1), pf.skoff);   // wavefronts 2, 3 repeat 0, 1
+    };
+    stage_block(0);
+    stage_block(1);
+    stage_block(2);
+
+    // line 5
+    const int8_t *qptr = Q + qrow * D + 16 * g;
+    v4i qf[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
+    float nq2 = sQ[qrow] * (-LOG2E * ACC_UNIT);
+    // The loads above must have landed BEFORE the loop as far as the compiler is concerned: a wait for them inside the
+    // loop would be a wait for every outstanding vector-memory operation, the staged copies included.
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+v"(qf[kk]));
+    asm volatile("" : "+v"(nq2));
+
+    // line 6: this wavefront's d tile of the running output (units of 2^26), m and l of the whole row
+    float m2 = -INFINITY, l = 0.0f, o[16];
+    v16i acc0;                                                   // what both accumulations start from
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { o[v] = 0.0f; acc0[v] = ACC_START_I; }
+
+    wait_vmcnt<2 * PER_BLOCK>();                                 // my pieces of block 0 have landed (blocks 1 and 2 may be in flight)
+    __syncthreads();                                             // everyone's have
+    for (int jb = 0; jb < nblocks; ++jb) {                       // line 7
+        const int st = jb % NSTAGE, j0 = jb * BC;
+        const lds_ptr ks = kbuf + st * BC * D, vs = vbuf + st * BC * D, sk = skbuf + st * BC * 4;
+
+        // line 9 for key tile `wave`
+        v4i kop[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) kop[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * wave * D);
+        v4f skv[4];
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) skv[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * wave + 32 * vq);
+        // (registers are plentiful here: the accumulators start from a register block holding the constant, and every
+        // MFMA is the compiler's own, with its dependency handling)
+        v16i sacc = acc0;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[kk], qf[kk], sacc, 0, 0, 0);
+        // kept keys: index inside the block <= klimit (the causal diagonal, the ragged end of the sequence)
+        const int tail = Nk - 1 - j0;
+        const int klimit = CAUSAL ? min(q_head + shift - j0, tail) : tail;
+        const bool masked = CAUSAL ? (j0 + BC - 1 > min(first_q + shift, Nk - 1)) : (tail < BC - 1);   // wave-uniform
+        float a[16], bmin = INFINITY;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float x = (ACC_START_F - __int_as_float(sacc[4 * vq + e])) * skv[vq][e];
+                if (masked && (32 * wave + 8 * vq + 4 * g + e > klimit)) x = INFINITY;
+                a[4 * vq + e] = x;
+                bmin = fminf(bmin, x);
+            }
+        bmin = pair_min(bmin);
+        if (g == 0) sm.ext[wave][r] = bmin;
+        __syncthreads();
+        // every wavefront is past the second GEMM of block jb - 1: the stage that block used takes block jb + 3
+        stage_block(jb + 3);
+        // line 10 over the whole block
+        bmin = fminf(fminf(sm.ext[0][r], sm.ext[1][r]), fminf(sm.ext[2][r], sm.ext[3][r]));
+        const float m_new = fmaxf(m2, bmin * nq2);
+        const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
+        const float mm = m_new - (IFA_PACK == 0 ? LOG2_R : LOG2_R_NORM);
+        m2 = m_new;
+        // line 11 for key tile `wave`
+        v4i pw;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            uint32_t w = 0;
+            if (IFA_PACK == 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[4 * vq + e], nq2, -mm)), e, w);
+            } else {
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[4 * vq + e], nq2, -mm));
+                typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                const us2 lo16 = __builtin_amdgcn_cvt_pknorm_u16(x[0], x[1]), hi16 = __builtin_amdgcn_cvt_pknorm_u16(x[2], x[3]);
+                w = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi16), __builtin_bit_cast(uint32_t, lo16), 0x06040200u);
+            }
+            pw[vq] = static_cast<int>(w);
+        }
+        sm.p[wave][lane] = pw;
+        wait_vmcnt<2 * PER_BLOCK>();                             // my pieces of block jb + 1 have landed (two later blocks may be in flight)
+        __syncthreads();                                         // everyone's have, and every P tile of this block is in LDS
+        // lines 12, 13: d tile `wave` of O^T = V^T P^T over the four key tiles, the row sum over the same P dwords
+        if (wave >= KS) continue;                                // D = 64: two d tiles; the other wavefronts only take part above
+        v16i pacc;
+        uint32_t psum = 0;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const v4i pf = sm.p[mt][lane];
+            const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, wave) + 32 * mt * D));
+            const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, wave) + 16 * D + 32 * mt * D));
+            const v4i vop = {t0[0], t0[1], t1[0], t1[1]};
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) psum = __builtin_amdgcn_sad_u8(static_cast<uint32_t>(pf[vq]), 0u, psum);
+            pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop, pf, mt == 0 ? acc0 : pacc, 0, 0, 0);
+        }
+        l = __builtin_fmaf(l, alpha, static_cast<float>(psum));
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[v] = __builtin_fmaf(o[v], alpha, -(ACC_START_F - __int_as_float(pacc[v])));
+    }
+    wait_all_memory();                                           // requests past the last block: nothing of mine stays in flight
+
+    // lines 15-17 for d tile `wave` (d = 32 * wave + 8 * (v / 4) + 4 * g + v % 4 of query r)
+    const float lt = l + swap32(l);
+    const float f = sV[head] * ACC_UNIT / lt;
+    if (q_head < Nq && wave < KS) {
+        OutT *orow = O + (static_cast<long>(head) * Nq + q_head) * D + 32 * wave + 4 * g;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            if constexpr (sizeof(OutT) == 2) {
+                *reinterpret_cast<uint2 *>(orow + 8 * vq) = Pack4<OutT>::pack(o[4 * vq] * f, o[4 * vq + 1] * f, o[4 * vq + 2] * f, o[4 * vq + 3] * f);
+            } else {
+                *reinterpret_cast<v4f *>(orow + 8 * vq) = v4f{o[4 * vq] * f, o[4 * vq + 1] * f, o[4 * vq + 2] * f, o[4 * vq + 3] * f};
+            }
+        }
+    }
+#endif
+}
+
 // ---- host side ----------------------------------------------------------------------------------
 hipStream_t g_stream = nullptr;
 
@@ -737,9 +943,30 @@ int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *s
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
+// Calls with at most this many queries per head go to the narrow kernel (measured against the kernel above).
+#ifndef IFA_NARROW_MAX_Q
+#define IFA_NARROW_MAX_Q 64
+#endif
+
+template <int D, bool CAUSAL, typename OutT>
+int launch_narrow(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
+                  int heads, int Nq, int Nk, void *O, hipStream_t st) {
+    const long wgs = static_cast<long>(heads) * ((Nq + NARROW_BR - 1) / NARROW_BR);
+    hipLaunchKernelGGL((int_flash_attn_fwd_narrow_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0, st,
+                       Q, K, V, sQ, sK, sV, heads, Nq, Nk, static_cast<OutT *>(O));
+    return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+}
+
 template <int D, bool CAUSAL, bool VB>
 int launch_fwd_dtype(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK,
                      const float *sV, int heads, int Nq, int Nk, void *O, int o_dtype, hipStream_t st) {
+    if (!VB && Nq <= IFA_NARROW_MAX_Q) {
+        switch (o_dtype) {
+        case IFA_F32: return launch_narrow<D, CAUSAL, float>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        case IFA_F16: return launch_narrow<D, CAUSAL, __half>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        default: return launch_narrow<D, CAUSAL, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        }
+    }
     switch (o_dtype) {
     case IFA_F32: return launch_fwd<D, CAUSAL, VB, float>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
     case IFA_F16: return launch_fwd<D, CAUSAL, VB, __half>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);

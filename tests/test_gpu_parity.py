@@ -448,6 +448,48 @@ def test_rectangular_rows_equal_the_square_kernel_rows(ifa):
         assert torch.equal(rect, full[:, :, N - Nq:])
 
 
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq", [1, 7, 32, 33, 64])
+def test_few_query_calls_equal_the_square_kernel_rows(ifa, Nq, d, out_dtype):
+    # A call with a few queries per head (a decode step, a short chunk) runs a kernel of its own that splits every key
+    # block over the wavefronts of a workgroup; it performs the arithmetic of the square kernel on the same operands, so
+    # its rows are the last Nq rows of the square problem bit for bit, with and without the mask, on a ragged length.
+    H, N = 5, 1231
+    rng = np.random.default_rng(Nq * 131 + d)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, N, d, score_sigma=2.0)
+    args = lambda q, sq: (dev(q[None]), dev(Kq[None]), dev(Vq[None]), dev(sq[None]), dev(sK[None]), dev(sV[None]))
+    for causal in (False, True):
+        full = ifa.int_flash_attn_fwd(*args(Qq, sQ), causal=causal, out_dtype=out_dtype)
+        few = ifa.int_flash_attn_fwd(*args(np.ascontiguousarray(Qq[:, N - Nq:]), np.ascontiguousarray(sQ[:, N - Nq:])),
+                                     causal=causal, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert torch.equal(few, full[:, :, N - Nq:]), (Nq, d, causal)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Nq,Nk,d", [(1, 16384, 128), (1, 1, 128), (7, 300, 64), (32, 4097, 128), (64, 127, 64), (50, 2048, 128)])
+def test_few_query_calls_against_the_oracle(ifa, Nq, Nk, d, causal):
+    # the same calls against Algorithm 1 itself, on several heads (8 heads: the XCD-aware mapping; 3: the plain one),
+    # with canary rows behind the output
+    if causal and Nk < Nq:
+        return
+    for H in (8, 3):
+        rng = np.random.default_rng(Nq + Nk + d + H)
+        Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, max(Nq, Nk), d, score_sigma=2.0)
+        Qq, sQ = np.ascontiguousarray(Qq[:, :Nq]), np.ascontiguousarray(sQ[:, :Nq])
+        Kq, Vq, sK = np.ascontiguousarray(Kq[:, :Nk]), np.ascontiguousarray(Vq[:, :Nk]), np.ascontiguousarray(sK[:, :Nk])
+        guard = 64
+        Obuf = torch.full((H * Nq + guard, d), 12345.0, dtype=torch.float32, device="cuda")
+        O = Obuf[:H * Nq].view(1, H, Nq, d)
+        ifa.int_flash_attn_fwd(dev(Qq[None]), dev(Kq[None]), dev(Vq[None]), dev(sQ[None]), dev(sK[None]), dev(sV[None]),
+                               causal=causal, out=O)
+        torch.cuda.synchronize()
+        assert bool((Obuf[H * Nq:] == 12345.0).all())
+        check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), Qq, Kq, Vq, sQ, sK, sV, causal,
+                             label=f"few queries Nq={Nq} Nk={Nk} d={d} H={H} causal={causal}")
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_random_int8_grid_inputs_wide_scores(ifa, causal):
     # int8 values over the whole range with score spreads from flat to nearly one-hot rows
