@@ -22,26 +22,28 @@
 // byte column i of the 8 rows addressed by the even lanes, lanes 8-15 of the rows addressed by the
 // odd lanes), two reads per MFMA operand, no VALU work.
 //
-// Softmax in base 2: log2(e) is folded into s_Q once per lane, the running max m2 is kept in log2
-// units and P = rint(exp2(acc * s_K * s_Q' - (m2 - log2 127))) with one v_exp_f32 per score and
-// v_cvt_pk_u8_f32 (round-half-even, measured) packing four P bytes per dword.
+// Softmax in base 2: log2(e) is folded into s_Q once per lane, the running max m2 is kept in log2 units and
+// P = rint(127 exp2(acc * s_K * s_Q' - m2)) with one v_exp_f32 per score; the exponent also carries log2(127 / 65535),
+// so that two v_cvt_pknorm_u16_f32 (round to nearest, measured) and one v_perm_b32 pack four P bytes into a dword.
 //
-// Schedule of one key block (what the issue-model micro-benchmark under csrc/microbench measured to be the fastest
-// arrangement of this instruction mix on a gfx950 SIMD shared by two wavefronts):
+// Schedule of one key block (the arrangement of this instruction mix that the issue-model micro-benchmark under
+// csrc/microbench measured fastest on a gfx950 SIMD shared by two wavefronts):
 //     M1  the 16 MFMAs of S^T back to back, into four accumulators that then become the scores in place
-//     V1  scores: minus bias, times s_K, running maximum          (vector ALU only)
-//     P0  P of the first 32-key tile: fma, exp2, pack             (vector ALU + transcendental unit)
+//     V1  scores: accumulator start taken off, times s_K, running extremum   (vector ALU only)
+//     P0  P of the first 32-key tile: fma, exp2, pack                        (vector ALU + transcendental unit)
 //     M2  the 16 MFMAs of O^T, key tile by key tile into four accumulators, with the P work of the NEXT key tile
-//         between them, at raised wave priority: v_exp_f32 costs the issue port little while MFMAs are in flight
+//         between them, at raised wave priority: up to three v_exp_f32 fit under an MFMA of the same wavefront for free
 //     --  wait for the staged copies, workgroup barrier, first K operands of the next block requested
 //     V3  the four accumulators folded into the running output
-// A wavefront in an MFMA stretch leaves the vector ALU to the other wavefront of its SIMD; on this chip an MFMA
-// and plain vector instructions issued by the SAME wavefront around it largely take turns instead of overlapping.
+// On this chip an MFMA and the plain vector instructions around it largely take turns instead of overlapping, whichever
+// of the two wavefronts of the SIMD issues them (a wavefront that waits for the matrix pipe holds back its own vector
+// stream behind it); only add, sub, mul and fma run at the full vector rate, everything else at half of it.
 //
-// The int32 results of both GEMMs are never converted: the accumulators start from a constant register block
-// holding the bit pattern of 1.5 * 2^23 (ACC_BIAS_I), so that a sum s reads as the float 1.5 * 2^23 + s, exactly,
-// and one fp32 subtraction recovers s.  The running output is kept negated so that its update is one three-address
-// fused multiply-add in place.
+// The int32 results of both GEMMs are never converted: each accumulation chain starts from the MFMA's INLINE constant
+// 1 / (2 pi) (bit pattern 0x3E22F983, in the middle of a binade where one integer step is 2^-26), so that a sum s reads
+// as the float 1 / (2 pi) + s 2^-26, exactly, and one v_sub_f32 against the same inline constant recovers s 2^-26;
+// no register holds the constant, and the 16 registers a constant block would take keep the query operands resident
+// for the whole key loop.  Scores and the running output are carried in those units of 2^-26.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
@@ -52,69 +54,9 @@
 #include "intfa_internal.h"
 #include "intfa_device.h"
 
-// experiment knobs (defaults are the shipped configuration)
+// Wave priority inside the second GEMM (s_setprio; default priority elsewhere): measured best at 3 on long sequences.
 #ifndef IFA_PRIO
 #define IFA_PRIO 3
-#endif
-#ifndef IFA_PIN
-#define IFA_PIN 1
-#endif
-#ifndef IFA_MIDBAR
-#define IFA_MIDBAR 1
-#endif
-#ifndef IFA_QRELOAD_MT
-#define IFA_QRELOAD_MT 2
-#endif
-#ifndef IFA_KPRE
-#define IFA_KPRE 1
-#endif
-#ifndef IFA_PRIO_M1
-#define IFA_PRIO_M1 0
-#endif
-#ifndef IFA_STAGE_IN
-#define IFA_STAGE_IN 1   /* staging copies issued 1: in M1, 2: in V1, 3: K pieces in V1 and V pieces early in M2, 4: K in M1, V in V1 */
-#endif
-#ifndef IFA_PUP
-#define IFA_PUP 1        /* P tiles computed before the second GEMM starts */
-#endif
-#ifndef IFA_PACK
-#define IFA_PACK 1       /* P to bytes: 0 = four v_cvt_pk_u8_f32 per dword, 1 = two v_cvt_pknorm_u16_f32 and one v_perm_b32 */
-#endif
-#ifndef IFA_FAKE_K
-#define IFA_FAKE_K 0     /* timing-only: 1 = no K operand reads in M1 (wrong results) */
-#endif
-#ifndef IFA_FAKE_SK
-#define IFA_FAKE_SK 0    /* timing-only: 1 = no s_K reads in V1 (wrong results) */
-#endif
-#ifndef IFA_FAKE_V
-#define IFA_FAKE_V 0     /* timing-only: 1 = V operands read once per block only (wrong results) */
-#endif
-#ifndef IFA_FAKE_STAGE
-#define IFA_FAKE_STAGE 0 /* timing-only: 1 = no staging copies in the block loop (stale LDS contents, wrong results) */
-#endif
-#ifndef IFA_STAMP
-#define IFA_STAMP 0
-#endif
-#if IFA_STAMP
-__device__ unsigned long long g_stamp[32];
-constexpr int STAMP_WAVES = 1 << 17;                       // per-wavefront records of the last launch: no atomics on the way out
-__device__ unsigned g_wave_rec[STAMP_WAVES][12];
-#ifndef IFA_LDS_PAD
-#define IFA_LDS_PAD 0    /* timing-only: extra LDS bytes per workgroup (forces one workgroup per CU) */
-#endif
-#if IFA_STAMP == 3   /* fine stamps inside M1 */
-#define STAMP2(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph2[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
-#else
-#define STAMP2(i) do { } while (0)
-#endif
-#if IFA_STAMP == 1 || IFA_STAMP == 3
-#define STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st.ph[i] += (unsigned)(t_ - st.t0); st.t0 = t_; } while (0)
-#else   /* 2: only the whole-kernel clock stamps */
-#define STAMP(i) do { } while (0)
-#endif
-#else
-#define STAMP(i) do { } while (0)
-#define STAMP2(i) do { } while (0)
 #endif
 
 namespace {
@@ -122,8 +64,7 @@ namespace {
 using namespace ifa_dev;
 
 constexpr int BC = 128;       // keys per block: the B_c of Algorithm 1
-[[maybe_unused]] constexpr float LOG2_R = 6.98868468677216585326f;   // log2(127)
-[[maybe_unused]] constexpr float LOG2_R_NORM = -9.01129329928057f;        // log2(127 / 65535)
+constexpr float LOG2_R_NORM = -9.01129329928057f;   // log2(127 / 65535): P / 65535 is what the 16-bit normalised conversion takes
 
 template <int D> struct Smem {
     alignas(4096) int8_t k[2][BC * D];   // K_j, row = key, 16-byte slots XOR-swizzled by row
@@ -243,11 +184,6 @@ template <int D> struct RowState {
     float m2;             // running max in log2 units (identical in lanes r and r + 32)
     float l;              // running sum of the rounded P over this lane's keys
     float o[D / 32][16];  // the running output in units of 2^26, d = 32*dt + 8*(v/4) + 4*g + v%4
-#if IFA_STAMP
-    unsigned long long t0;
-    unsigned ph[8];
-    unsigned ph2[12];
-#endif
 };
 
 // Lines 9-13 of Algorithm 1 for one key block already resident in LDS.  DIAG: a block with masked keys --
@@ -260,14 +196,14 @@ template <int D> struct RowState {
 // !DIAG blocks also carry the block-to-block hand-over: they request the staging copies of the next block during
 // M1, wait for them and meet the workgroup barrier between M2 and V3 (by then this wavefront has read everything
 // it needs from the current buffers), and, if `preload_next`, request the first K operands of the next block right
-// after the barrier so that their LDS latency is covered by V3.  `kfirst` holds those operands on entry (when
-// `kfirst_valid`) and on exit.  DIAG blocks leave staging and barriers to the caller: a wavefront whose rows see
-// none of a masked block skips it altogether.
+// after the barrier so that their LDS latency is covered by V3.  `kfirst` holds those operands on entry and on
+// exit.  DIAG blocks leave staging and barriers to the caller: a wavefront whose rows see none of a masked block
+// skips it altogether.  In !DIAG blocks the issue order is pinned (sched_group_barrier) to the one written here.
 template <int D, bool DIAG, bool VB, bool DBG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, lds_ptr ks_next, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float nq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
                                               int g, float oscale, const Prefetch &nx, bool preload_next,
-                                              v4i (&kfirst)[IFA_KPRE][D / 32], RowState<D> &st, const DebugDump &dbg, long dbg_row, int dbg_j0, int dbg_jb, int dbg_nq) {
+                                              v4i (&kfirst)[D / 32], RowState<D> &st, const DebugDump &dbg, long dbg_row, int dbg_j0, int dbg_jb, int dbg_nq) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
 
@@ -276,11 +212,6 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         for (int kk = 0; kk < KS; ++kk) dst[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(base, lo, kk) + 32 * mt * D);
     };
     auto load_sk = [&](v4f (&dst)[4], int mt) {
-        if (IFA_FAKE_SK && !DIAG) {
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) { dst[vq] = v4f{nq2, nq2 * 0.5f, nq2 * 0.25f, nq2}; asm volatile("" : "+v"(dst[vq])); }
-            return;
-        }
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) dst[vq] = *reinterpret_cast<LDS_AS const v4f *>(sk + lo.sk + 128 * mt + 32 * vq);
     };
@@ -290,56 +221,33 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     v16i sacc[4];
     v4i kop[2][KS];
     v4f skr[2][4];
-    constexpr int KPRE = DIAG ? 1 : IFA_KPRE;       // key tiles whose operands are in registers before the first MFMA
-    if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(IFA_PRIO_M1);
     if (DIAG) load_k(kop[0], ks, 0);
     else {
 #pragma unroll
-        for (int t = 0; t < KPRE; ++t)
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) kop[t][kk] = kfirst[t][kk];
+        for (int kk = 0; kk < KS; ++kk) kop[0][kk] = kfirst[kk];
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         if (mt <= last) {
-            if (KPRE == 1 && mt + 1 <= last && !(IFA_FAKE_K && !DIAG)) load_k(kop[(mt + 1) & 1], ks, mt + 1);
+            if (mt + 1 <= last) load_k(kop[(mt + 1) & 1], ks, mt + 1);
             // the scales of the first two key tiles are requested under the last MFMAs, so that V1 starts on data
             if (DIAG ? mt == last : mt == 2) load_sk(skr[0], 0);
             if (DIAG ? (mt == last && last >= 1) : mt == 3) load_sk(skr[1], 1);
-            if (!DIAG) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt); }
-            sacc[mt] = mfma_i8_start(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][0], qf[0]);
+            sacc[mt] = mfma_i8_start(kop[mt & 1][0], qf[0]);
 #pragma unroll
             for (int kk = 1; kk < KS; ++kk)
-                sacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[(IFA_FAKE_K && !DIAG) ? 0 : (mt & 1)][kk], qf[kk], sacc[mt], 0, 0, 0);
-            if (IFA_FAKE_K && !DIAG) {
-#pragma unroll
-                for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+v"(kop[0][kk]));
+                sacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[mt & 1][kk], qf[kk], sacc[mt], 0, 0, 0);
+            if (!DIAG) {                                                    // issue order: operand reads, then this tile's MFMAs
+                if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
+                else if (mt == 2) __builtin_amdgcn_sched_group_barrier(0x100, KS + 4, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, KS - 1, 0);     // (the chain start is an asm statement, not counted)
             }
-            if (KPRE == 2 && mt + 2 <= last) load_k(kop[mt & 1], ks, mt + 2);   // into the registers these MFMAs have read
-            if (!DIAG && IFA_PIN) {                                         // issue order: operand reads, then this tile's MFMAs
-                if (KPRE == 1) {
-                    if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 0 : KS, 0);
-                    else if (mt == 2) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_K ? 4 : KS + 4, 0);
-                    else __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, KS - 1, 0);
-                } else {
-                    if (mt >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, KS - 1, 0);
-                    if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
-                }
-            }
-            if (!DIAG && IFA_STAMP == 3) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt + 1); }
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 1 && !IFA_FAKE_STAGE) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
-            if (!DIAG && (mt & 1) == 0 && IFA_STAGE_IN == 1 && IFA_FAKE_STAGE == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }   // timing-only: half of the copies
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 4) prefetch_k_piece<D>(nx, lo, wave, mt);
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 5) prefetch_v_piece<D>(nx, lo, wave, mt);
-            if (!DIAG && IFA_STAMP == 3) { __builtin_amdgcn_sched_barrier(0); STAMP2(3 * mt + 2); }
+            if (!DIAG && mt < KS) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
         }
     }
-    if (!DIAG && (IFA_STAGE_IN == 1 || IFA_STAGE_IN == 4 || IFA_STAGE_IN == 5) && !IFA_FAKE_STAGE) prefetch_sk(nx, wave, lane);
-    if (IFA_PRIO_M1) __builtin_amdgcn_s_setprio(0);
+    if (!DIAG) prefetch_sk(nx, wave, lane);
     __builtin_amdgcn_sched_barrier(0);
-    STAMP(0);
 
     if (DBG && dbg.S) {
 #pragma unroll
@@ -375,14 +283,9 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             if (DIAG && mt >= clear_tiles) scale_elems(mt, skr[mt & 1], std::true_type{});
             else scale_elems(mt, skr[mt & 1], std::false_type{});
             if (mt + 2 <= last) load_sk(skr[mt & 1], mt + 2);    // into the registers this tile has just read
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 2) { prefetch_k_piece<D>(nx, lo, wave, mt); prefetch_v_piece<D>(nx, lo, wave, mt); }
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 3) prefetch_k_piece<D>(nx, lo, wave, mt);
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 4) prefetch_v_piece<D>(nx, lo, wave, mt);
-            if (!DIAG && mt < KS && IFA_STAGE_IN == 5) prefetch_k_piece<D>(nx, lo, wave, mt);
-            if (!DIAG && mt == 3 && (IFA_STAGE_IN == 2 || IFA_STAGE_IN == 3)) prefetch_sk(nx, wave, lane);
-            if (!DIAG && IFA_PIN) {                                         // 16 subtractions, 16 multiplies, 8 three-way minima per tile
+            if (!DIAG) {                                         // 16 subtractions, 16 multiplies, 8 three-way minima per tile
                 __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);
-                if (mt < 2 && !IFA_FAKE_SK) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                if (mt < 2) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             }
         } else {
 #pragma unroll
@@ -390,35 +293,25 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
         }
     }
     if (!DIAG) __builtin_amdgcn_sched_barrier(0);
-    STAMP(1);
 
     // line 10
     bmin = pair_min(bmin);
     const float m_new = fmaxf(st.m2, bmin * nq2);
     const float alpha = __builtin_amdgcn_exp2f(st.m2 - m_new);   // exp2(-inf) = 0 on the first block
-    const float mm = m_new - (IFA_PACK == 0 ? LOG2_R : LOG2_R_NORM);
+    const float mm = m_new - LOG2_R_NORM;
     st.m2 = m_new;
 
-    // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order, one dword at a time
+    // line 11: P = rint(127 * 2^(a*s_Q' - m_new)), 4 keys per dword in accumulator order, one dword at a time.
+    // The exponent carries log2(127 / 65535), so that the value is P / 65535 and the conversion to a 16-bit normalised
+    // integer rounds it to P (to nearest; measured): two conversions give the four P of a dword in bytes 0 and 2 of two
+    // registers, one byte permute gathers them -- three half-rate instructions where v_cvt_pk_u8_f32 takes four.
     v4i pf[4];
     uint32_t psum = 0;
     auto p_dword = [&](int mt, int vq) {
-        uint32_t w = 0;
-        if (IFA_PACK == 0) {
+        float x[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm)), e, w);
-        } else {
-            // The exponent carries log2(127 / 65535), so that the value is P / 65535 and the conversion to a 16-bit
-            // normalised integer rounds it to P (to nearest; measured): two conversions give the four P of this dword in
-            // bytes 0 and 2 of two registers, one byte permute gathers them -- three half-rate instructions for four.
-            float x[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm));
-            typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-            const us2 lo = __builtin_amdgcn_cvt_pknorm_u16(x[0], x[1]), hi = __builtin_amdgcn_cvt_pknorm_u16(x[2], x[3]);
-            w = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x06040200u);
-        }
+        for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][4 * vq + e], nq2, -mm));
+        uint32_t w = pack_p4(x);
         if (DBG && dbg.P_in) {
             const int key = dbg_j0 + 32 * mt + 8 * vq + 4 * g;
             w = (dbg_row < dbg_nq && key + 3 < dbg.Nk) ? *reinterpret_cast<const uint32_t *>(dbg.P_in + dbg_row * dbg.Nk + key) : 0u;
@@ -430,14 +323,10 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
             if (dbg_row < dbg_nq && key + 3 < dbg.Nk) *reinterpret_cast<uint32_t *>(dbg.P + dbg_row * dbg.Nk + key) = w;
         }
     };
-    // ---- P0
+    // ---- P0: the first key tile's P
 #pragma unroll
-    for (int t = 0; t < IFA_PUP; ++t)
-        if (t <= last)
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) p_dword(t, vq);
+    for (int vq = 0; vq < 4; ++vq) p_dword(0, vq);
     __builtin_amdgcn_sched_barrier(0);
-    STAMP(2);
 
     // ---- M2: line 13, O^T = V^T P^T key tile by key tile into DT accumulators; between the MFMAs of key tile mt
     // the P dwords of key tile mt + 1.  One V^T operand (two transposing reads) per MFMA, requested one key tile ahead
@@ -459,20 +348,16 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 pacc[dt] = mt == 0 ? mfma_i8_start(vop[dt], pf[0]) : __builtin_amdgcn_mfma_i32_32x32x32_i8(vop[dt], pf[mt], pacc[dt], 0, 0, 0);
-                if (!DIAG && IFA_PIN && mt > 0) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (!DIAG && IFA_STAGE_IN == 3 && mt == 0 && dt < KS) prefetch_v_piece<D>(nx, lo, wave, dt);
+                if (!DIAG && mt > 0) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (mt + 1 <= last) {
-                    if (!(IFA_FAKE_V && !DIAG)) load_v(mt + 1, dt);
-                    else asm volatile("" : "+v"(vop[dt]));
-                    if (!DIAG && IFA_PIN) __builtin_amdgcn_sched_group_barrier(0x100, IFA_FAKE_V ? 0 : 2, 0);
-                }
-                if (mt + IFA_PUP <= last) {
+                    load_v(mt + 1, dt);
+                    if (!DIAG) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-                    for (int q = 0; q < 4 / DT; ++q) p_dword(mt + IFA_PUP, dt * (4 / DT) + q);
-                    if (!DIAG && IFA_PIN) {                                 // issue order: 4 fma, 4 exp2, 4 pack + row sum per dword
+                    for (int q = 0; q < 4 / DT; ++q) p_dword(mt + 1, dt * (4 / DT) + q);
+                    if (!DIAG) {                                            // issue order: 4 fma, 4 exp2, 2 + 1 pack and the row sum per dword
                         __builtin_amdgcn_sched_group_barrier(0x002, 4 * (4 / DT), 0);
                         __builtin_amdgcn_sched_group_barrier(0x400, 4 * (4 / DT), 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, (IFA_PACK == 0 ? 5 : 4) * (4 / DT), 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4 * (4 / DT), 0);
                     }
                 }
             }
@@ -480,23 +365,19 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     }
     if (!DIAG) __builtin_amdgcn_sched_barrier(0);
     if (IFA_PRIO) __builtin_amdgcn_s_setprio(0);
+    if (DIAG) {
+        // A wavefront that sees one key tile of a masked block ends every accumulation chain with its first MFMA, the
+        // assembly statement the compiler does not know to be an MFMA: give those results time to land before the
+        // fold reads them (everywhere else a chain ends with an MFMA of the compiler's own, which it waits for).
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15");
+        __builtin_amdgcn_sched_barrier(0);
+    }
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
-    STAMP(3);
 
-    if (!DIAG && IFA_MIDBAR) {
+    if (!DIAG) {
         wait_all_memory();                                       // my part of the next block has landed in LDS
-        STAMP(4);
         __syncthreads();                                         // everyone's has, and the current buffers are free again
-        STAMP(5);
-        if (preload_next) {
-#pragma unroll
-            for (int t = 0; t < IFA_KPRE; ++t) load_k(kfirst[t], ks_next, t);
-        }
-        if (IFA_STAGE_IN == 6) {     // the buffers of this block are free: the block after next goes there, a whole block ahead of its use
-#pragma unroll
-            for (int i = 0; i < KS; ++i) { prefetch_k_piece<D>(nx, lo, wave, i); prefetch_v_piece<D>(nx, lo, wave, i); }
-            prefetch_sk(nx, wave, lane);
-        }
+        if (preload_next) load_k(kfirst, ks_next, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -521,17 +402,6 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
 #pragma unroll
         for (int v = 0; v < 16; ++v)
             st.o[dt][v] = __builtin_fmaf(st.o[dt][v], alpha_o, -(ACC_START_F - __int_as_float(pacc[dt][v])));
-    STAMP(6);
-    if (!DIAG && !IFA_MIDBAR) {
-        wait_all_memory();
-        STAMP(4);
-        __syncthreads();
-        STAMP(5);
-        if (preload_next) {
-#pragma unroll
-            for (int t = 0; t < IFA_KPRE; ++t) load_k(kfirst[t], ks_next, t);
-        }
-    }
 }
 
 #endif  // __HIP_DEVICE_COMPILE__
@@ -544,14 +414,6 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #if defined(__HIP_DEVICE_COMPILE__)
     __shared__ Smem<D> sm;
     constexpr int DT = D / 32;
-#if IFA_STAMP
-    const unsigned long long k_c0 = __builtin_readcyclecounter(), k_w0 = __builtin_amdgcn_s_memrealtime();
-#if IFA_LDS_PAD
-    __shared__ int lds_pad[IFA_LDS_PAD / 4];
-    if (Nq < 0) lds_pad[threadIdx.x] = Nk;     // never true: keeps the array allocated
-    if (Nq < -1) O[0] = static_cast<OutT>(static_cast<float>(lds_pad[threadIdx.x ^ 1]));
-#endif
-#endif
 
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
@@ -595,13 +457,6 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 #pragma unroll
         for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(first, lo, wave, i); prefetch_v_piece<D>(first, lo, wave, i); }
         prefetch_sk(first, wave, lane);
-        if (IFA_STAGE_IN == 6) {                                 // ... and for block 1 (a request past the last block fetches nothing)
-            const bool two = nblocks > 1;
-            const Prefetch second = {rK, rV, rSK, two ? BC * D : NOWHERE, two ? BC * 4 : NOWHERE, kbuf + BC * D, vbuf + BC * D, skbuf + BC * 4};
-#pragma unroll
-            for (int i = 0; i < D / 32; ++i) { prefetch_k_piece<D>(second, lo, wave, i); prefetch_v_piece<D>(second, lo, wave, i); }
-            prefetch_sk(second, wave, lane);
-        }
     }
 
     // line 6
@@ -620,40 +475,26 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
 
     wait_all_memory();
     __syncthreads();
-    v4i kfirst[IFA_KPRE][D / 32];                                // K operands of the first key tile(s) of the coming block
+    v4i kfirst[D / 32];                                          // K operands of the first key tile of the coming block
 #pragma unroll
-    for (int t = 0; t < IFA_KPRE; ++t)
-#pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk)
-            kfirst[t][kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(kbuf, lo, kk) + 32 * t * D);
+    for (int kk = 0; kk < D / 32; ++kk) kfirst[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(kbuf, lo, kk));
 
     // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_c]
     const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
     float sv_prev = 1.0f;
-#if IFA_STAMP
-    for (int i = 0; i < 8; ++i) st.ph[i] = 0;
-    for (int i = 0; i < 12; ++i) st.ph2[i] = 0;
-    st.t0 = __builtin_readcyclecounter();
-#endif
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
         const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
         const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
         sv_prev = sv_j;
-        // line 8, asynchronous: for the next block into the other buffers, or (IFA_STAGE_IN == 6) for the block after next
-        // into this block's own buffers once the barrier inside has freed them
-        const int ahead = IFA_STAGE_IN == 6 ? 2 : 1, dst = IFA_STAGE_IN == 6 ? cur : nxt;
-        const int j1 = (jb + ahead) * BC;
-        const bool more = jb + ahead < nblocks;
-        const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + dst * BC * D,
-                             vbuf + dst * BC * D, skbuf + dst * BC * 4};
+        const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
+        const bool more = jb + 1 < nblocks;
+        const Prefetch pf = {rK, rV, rSK, more ? j1 * D : NOWHERE, more ? j1 * 4 : NOWHERE, kbuf + nxt * BC * D,
+                             vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
         // the staged copies are awaited and the workgroup barrier is met inside, between the second GEMM and the fold
         process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, nq2,
                                          wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
     }
-#if IFA_STAMP
-    const unsigned long long k_c1 = __builtin_readcyclecounter(), k_w1 = __builtin_amdgcn_s_memrealtime();   // end of the main loop
-#endif
     // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
     // ragged last block is one of them or, without a mask, the only one).  They are written out one after the
     // other rather than as a loop so that the staging offsets are dead once the second one has been requested.
@@ -677,7 +518,7 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     };
     if (nfull < nblocks) {
         const bool second = nfull + 1 < nblocks;
-        if (second && IFA_STAGE_IN != 6) {                       // line 8 for the second masked block
+        if (second) {                                            // line 8 for the second masked block
             const int nxt = (nfull & 1) ^ 1, j1 = (nfull + 1) * BC;
             const Prefetch pf = {rK, rV, rSK, j1 * D, j1 * 4, kbuf + nxt * BC * D, vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
 #pragma unroll
@@ -697,30 +538,11 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     const float f = (VB ? sv_prev : sVh[0]) * ACC_UNIT / l;      // st.o holds O 2^-26 (in units of the last block's scale if VB)
     // The buffers the last block did not use are free for every wavefront since the barrier before it: each
     // wavefront stages its tile in its own 64 D bytes of them and stores whole (fp32: half) rows.
-    if (IFA_STAGE_IN == 6) {   // requests past the last block (they move no tensor data) may still be in flight into these buffers
-        wait_all_memory();
-        __syncthreads();
-    }
     const int freeb = nblocks & 1;
     const lds_ptr stage = (wave < 2 ? kbuf : vbuf) + freeb * BC * D + (wave & 1) * (64 * D);
     const int row0 = qb * BR + 32 * wave;                        // first query row of this wavefront
     OutT *orow0 = O + (static_cast<long>(head) * Nq + row0) * D;
     store_tile_staged<D, OutT>(stage, orow0, Nq - row0, lane, [&](int dt, int v) { return st.o[dt][v] * f; });
-#if IFA_STAMP
-    {
-        const unsigned long long k_c2 = __builtin_readcyclecounter(), k_w2 = __builtin_amdgcn_s_memrealtime();
-        const long wid = static_cast<long>(blockIdx.x) * 4 + wave;
-        if (lane == 0 && wid < STAMP_WAVES) {
-            unsigned *r = g_wave_rec[wid];
-            for (int i = 0; i < 7; ++i) r[i] = st.ph[i];
-            r[7] = static_cast<unsigned>(nfull);
-            r[8] = static_cast<unsigned>(k_c2 - k_c0);          // whole kernel, cycles
-            r[9] = static_cast<unsigned>(k_w2 - k_w0);          // whole kernel, 100 MHz ticks
-            r[10] = static_cast<unsigned>(k_c1 - k_c0) - (st.ph[0] + st.ph[1] + st.ph[2] + st.ph[3] + st.ph[4] + st.ph[5] + st.ph[6]);   // before the main loop
-            r[11] = static_cast<unsigned>(k_c2 - k_c1);         // after the main loop: masked blocks and epilogue
-        }
-    }
-#endif
 #endif
 }
 
@@ -869,25 +691,16 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
         bmin = fminf(fminf(sm.ext[0][r], sm.ext[1][r]), fminf(sm.ext[2][r], sm.ext[3][r]));
         const float m_new = fmaxf(m2, bmin * nq2);
         const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
-        const float mm = m_new - (IFA_PACK == 0 ? LOG2_R : LOG2_R_NORM);
+        const float mm = m_new - LOG2_R_NORM;
         m2 = m_new;
         // line 11 for key tile `wave`
         v4i pw;
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-            uint32_t w = 0;
-            if (IFA_PACK == 0) {
+            float x[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_exp2f(__builtin_fmaf(a[4 * vq + e], nq2, -mm)), e, w);
-            } else {
-                float x[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[4 * vq + e], nq2, -mm));
-                typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-                const us2 lo16 = __builtin_amdgcn_cvt_pknorm_u16(x[0], x[1]), hi16 = __builtin_amdgcn_cvt_pknorm_u16(x[2], x[3]);
-                w = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi16), __builtin_bit_cast(uint32_t, lo16), 0x06040200u);
-            }
+            for (int e = 0; e < 4; ++e) x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(a[4 * vq + e], nq2, -mm));
+            const uint32_t w = pack_p4(x);
             pw[vq] = static_cast<int>(w);
         }
         sm.p[wave][lane] = pw;
@@ -1092,14 +905,3 @@ extern "C" int ifa_debug_fwd(const signed char *Q_i8, const signed char *K_i8, c
     return causal ? launch_debug<64, true>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st) : launch_debug<64, false>(Q, K, V, s_Q, s_K, s_V, N, dbg, O, st);
 }
 
-#if IFA_STAMP
-extern "C" int ifa_debug_read_wave_records(unsigned *out, long waves) {
-    if (waves > STAMP_WAVES) return IFA_ERR_SHAPE;
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wave_rec), waves * 48) == hipSuccess ? IFA_OK : IFA_ERR_HIP;
-}
-extern "C" int ifa_debug_read_stamps(unsigned long long *out16, int reset) {
-    if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_stamp), 256) != hipSuccess) return IFA_ERR_HIP;
-    if (reset) { unsigned long long z[32] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_stamp), z, 256) != hipSuccess) return IFA_ERR_HIP; }
-    return IFA_OK;
-}
-#endif

@@ -118,6 +118,14 @@ __device__ __forceinline__ v16i mfma_i8_start(const v4i &a, const v4i &b) {
     return d;
 }
 
+// Four P values, given as P / 65535, rounded to nearest and packed into the four bytes of a dword (key order):
+// v_cvt_pknorm_u16_f32 twice (P in bytes 0 and 2 of each result), one v_perm_b32.
+__device__ __forceinline__ uint32_t pack_p4(const float (&x)[4]) {
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    const us2 lo = __builtin_amdgcn_cvt_pknorm_u16(x[0], x[1]), hi = __builtin_amdgcn_cvt_pknorm_u16(x[2], x[3]);
+    return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, hi), __builtin_bit_cast(uint32_t, lo), 0x06040200u);
+}
+
 // max (min) over the lane pair (r, r + 32) with v_permlane32_swap: no LDS round trip
 __device__ __forceinline__ float pair_max(float x) {
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
