@@ -53,6 +53,10 @@ def main():
                          "vblock: Algorithm 1 with one V scale per key block (the paper's stated next step)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="profiling aid, not a benchmark: all-zero activations, i.e. the same instruction stream on operands "
+                         "that toggle no bits -- the difference to the real run is what the clock the chip settles at under "
+                         "real data costs (implies --no-cpu-baseline; the JSON line says so in config.workload)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (known HBM traffic, "
                          "to calibrate the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -78,7 +82,11 @@ def main():
     Q = torch.empty(sh, dtype=tdtype, device=dev)
     K = torch.empty_like(Q)
     V = torch.empty_like(Q)
-    for h in range(w.heads):
+    if args.zero_operands:
+        args.no_cpu_baseline = True
+        for t in (Q, K, V):
+            t.zero_()
+    for h in range(0 if args.zero_operands else w.heads):
         b, hh = divmod(h, w.H)
         Q[b, hh].copy_(torch.from_numpy(workloads.head_tensor(w, "Q", h)))
         K[b, hh].copy_(torch.from_numpy(workloads.head_tensor(w, "K", h)))
@@ -166,7 +174,7 @@ def main():
         "metric": "int8_attention_fwd_tops", "value": round(tops_step, 2), "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "prewarm_steps": prewarm_steps, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if w.causal else 'non-causal'} "
+        "config": {"workload": ("ALL-ZERO OPERANDS (profiling aid) in the shape of " if args.zero_operands else "") + f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if w.causal else 'non-causal'} "
                                f"{w.dist} {w.in_dtype} in, {w.out_dtype} out; step = "
                                + ("quantize Q,K + half-INT8 fused attention (fp16 V)" if half else
                                   "quantize Q,K,V (V per key block) + fused attention" if vblock else "quantize Q,K,V + fused attention"),
