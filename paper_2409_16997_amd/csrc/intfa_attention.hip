@@ -160,8 +160,9 @@ struct Prefetch {
     lds_ptr lk, lv, lsk;             // LDS destinations (tile bases)
 };
 // Block offset of a request that must fetch nothing (no block follows): past the end of any tensor, so that every
-// lane is out of range -- the scalar offset takes part in the range check (probed on this chip) -- and the copy
-// moves no data.  Cheaper than a branch around each copy: the block stays one basic block for the scheduler.
+// lane is out of range -- the scalar offset takes part in the range check (probed on this chip) -- and nothing is
+// read from memory.  The LDS destination IS still written (with zeros), so it must be a buffer nobody uses until the
+// next wait + barrier.  Cheaper than a branch around each copy: the block stays one basic block for the scheduler.
 constexpr int NOWHERE = 0x7fff0000;
 
 template <int D>
