@@ -31,7 +31,8 @@ typedef enum {
     IFA_ERR_SHAPE = -2,       /* a size is <= 0 or overflows the index range                  */
     IFA_ERR_DTYPE = -3,       /* dtype enum out of range                                      */
     IFA_ERR_UNSUPPORTED = -4, /* valid but not built: d, N granularity, misaligned pointer    */
-    IFA_ERR_HIP = -5          /* the HIP runtime refused the launch (hipGetLastError != 0)    */
+    IFA_ERR_HIP = -5,         /* the HIP runtime refused the launch (hipGetLastError != 0)    */
+    IFA_ERR_WORKSPACE = -6    /* the shape needs more workspace than the caller gave          */
 } ifa_status;
 
 /* Human-readable name of a status code (static storage, never null). */
@@ -141,6 +142,26 @@ int int_flash_attn_fwd_ex(const signed char *Q_i8, const signed char *K_i8, cons
 int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                             const float *s_Q, const float *s_K, const float *s_V,
                             int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream);
+
+/*
+ * Algorithm 1 for a FEW queries per head against many keys (a decode step, a few speculative tokens), with the key
+ * axis of every head split over the whole chip.  Shapes, mask rule and error rules of int_flash_attn_fwd_rect, with
+ * Nq <= 8 (else IFA_ERR_UNSUPPORTED).  Lines 9-10 run first for every key block (the scaled scores and the block
+ * maxima go to the workspace), so that each part of the key axis forms P on the grid of the running maximum the
+ * sequential walk of Algorithm 1 would have at that block: P and the int32 P V are those of int_flash_attn_fwd_rect
+ * bit for bit, and O differs from its result only by the order of the fp32 additions of lines 12-13 (the partial
+ * (m, l, O) of the parts are merged with e^{m_part - m}, once per part instead of once per block).
+ *   workspace         device memory, 256-byte aligned, at least ifa_splitk_workspace_bytes(B, H, Nq, Nk, d) bytes
+ *                     (else IFA_ERR_WORKSPACE); owned by the caller, contents undefined before and after, must not be
+ *                     shared by calls that may overlap.  Three kernel launches on hip_stream, nothing is allocated.
+ * ifa_splitk_workspace_bytes returns 0 for a shape this entry point does not take.
+ */
+long ifa_splitk_workspace_bytes(int B, int H, int Nq, int Nk, int d);
+
+int int_flash_attn_fwd_splitk(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                              const float *s_Q, const float *s_K, const float *s_V,
+                              int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype,
+                              void *workspace, long workspace_bytes, void *hip_stream);
 
 /*
  * Per-block quantization of V -- the scheme the paper names as its next step (Section 3.2, footnote;

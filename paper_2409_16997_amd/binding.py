@@ -23,6 +23,8 @@ SIGNATURES = {
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
+    "ifa_splitk_workspace_bytes": (_l, [_i] * 5),
+    "int_flash_attn_fwd_splitk": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp, _l, _vp]),
     "quantize_blockwise": (_i, [_vp, _i, _l, _l, _i, _i, _vp, _vp, _vp]),
     "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_vblock_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
@@ -172,6 +174,36 @@ def int_flash_attn_fwd(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=
     else:
         code = lib().int_flash_attn_fwd_ex(*args, B, H, N, *tail)
     _check(code, "int_flash_attn_fwd")
+    return out
+
+
+def splitk_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int) -> int:
+    """Bytes of workspace int_flash_attn_fwd_splitk needs for this shape (0: the shape is not one it takes)."""
+    return int(lib().ifa_splitk_workspace_bytes(int(B), int(H), int(Nq), int(Nk), int(d)))
+
+
+def int_flash_attn_fwd_splitk(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None, workspace=None):
+    """Algorithm 1 for at most 8 queries per head against many keys (a decode step), the key axis split over the
+    whole chip: same shapes and mask convention as int_flash_attn_fwd.  `workspace`: a uint8 device tensor of at least
+    splitk_workspace_bytes(...) bytes (allocated here if not given)."""
+    import torch
+    B, H, N, d = Q_i8.shape
+    Nk = K_i8.shape[2]
+    if K_i8.shape != (B, H, Nk, d) or V_i8.shape != K_i8.shape or s_K.shape != (B, H, Nk) or s_Q.shape != (B, H, N) \
+            or s_V.shape != (B, H):
+        raise IntfaError("Q/K/V/scale shapes do not agree")
+    if out is None:
+        out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
+    need = splitk_workspace_bytes(B, H, N, Nk, d)
+    if need == 0:
+        raise IntfaError("int_flash_attn_fwd_splitk: shape not supported (at most 8 queries per head, d in {64, 128})")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q_i8.device)
+    code = lib().int_flash_attn_fwd_splitk(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
+                                           _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32),
+                                           B, H, N, Nk, d, int(bool(causal)), _dev(out), _dtype_enum(out),
+                                           _dev(workspace, torch.uint8), workspace.numel(), _stream())
+    _check(code, "int_flash_attn_fwd_splitk")
     return out
 
 

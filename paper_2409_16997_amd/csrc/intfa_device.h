@@ -84,6 +84,12 @@ __device__ __forceinline__ void lds_copy16(const BufRsrc &r, lds_ptr lds, unsign
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
 }
+// the same with the non-temporal hint: for bytes that are read exactly once (the streaming passes of the key-split path)
+__device__ __forceinline__ void lds_copy16_nt(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
+    const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
+                 :: "s"(static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds))), "v"(voff), "s"(rs), "s"(soff) : "m0");
+}
 // 64 lanes x 4 bytes, lane t's dword lands at lds + 4 t
 __device__ __forceinline__ void lds_copy4(const BufRsrc &r, lds_ptr lds, unsigned voff, int soff) {
     const v4i rs = {r.w[0], r.w[1], r.w[2], r.w[3]};

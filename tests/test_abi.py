@@ -21,13 +21,13 @@ def L():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "intfa.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(?:int|const char \*)\s*\*?\s*(\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(?:int|long|const char \*)\s*\*?\s*(\w+)\s*\(", text)))
 
 
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_headwise_ex", "quantize_qkv", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_headwise_ex", "quantize_qkv", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "int_flash_attn_fwd_splitk", "ifa_splitk_workspace_bytes", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -41,7 +41,7 @@ def test_library_exports_every_declared_symbol(L):
 
 def test_status_strings(L):
     assert L.ifa_status_str(0) == b"IFA_OK"
-    for c in (-1, -2, -3, -4, -5):
+    for c in (-1, -2, -3, -4, -5, -6):
         assert L.ifa_status_str(c).startswith(b"IFA_ERR_")
     assert L.ifa_status_str(7) == b"unknown ifa_status"
 
@@ -92,6 +92,16 @@ def test_argument_validation_happens_on_the_host(L):
     rc = L.int_flash_attn_fwd_rect
     assert rc(p, p, p, p, p, p, 1, 1, 256, 64, 128, 1, p, 1, None) == -4             # causal with Nk < Nq
     assert rc(p, p, p, p, p, p, 1, 1, 0, 64, 128, 0, p, 1, None) == -2 and rc(p, p, p, p, p, null, 1, 1, 8, 64, 128, 0, p, 1, None) == -1
+    sk, wb = L.int_flash_attn_fwd_splitk, L.ifa_splitk_workspace_bytes
+    ws = ctypes.c_void_p(0x10000)
+    assert wb(1, 8, 1, 16384, 128) > 4 * 8 * 16384 and wb(1, 8, 9, 16384, 128) == 0 and wb(1, 8, 1, 16384, 96) == 0
+    need = wb(1, 8, 4, 1000, 128)
+    assert sk(p, p, p, p, p, p, 1, 8, 9, 1000, 128, 0, p, 1, ws, 1 << 30, None) == -4       # more than 8 queries
+    assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, null, need, None) == -1
+    assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, ws, need - 1, None) == -6       # workspace too small
+    assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, odd, need, None) == -4          # workspace not 256-byte aligned
+    assert sk(p, p, p, p, p, p, 1, 8, 4, 2, 128, 1, p, 1, ws, need, None) == -4              # causal with Nk < Nq
+    assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 5, ws, need, None) == -3
     hf = L.int_flash_attn_fwd_half
     assert hf(p, p, null, p, p, 1, 1, 128, 128, 0, p, 1, None) == -1 and hf(p, p, p, p, p, 1, 0, 128, 128, 0, p, 1, None) == -2
     assert hf(p, p, p, p, p, 1, 1, 128, 128, 0, p, -1, None) == -3 and hf(p, p, p, p, p, 1, 1, 128, 256, 0, p, 1, None) == -4

@@ -490,6 +490,50 @@ def test_few_query_calls_against_the_oracle(ifa, Nq, Nk, d, causal):
                              label=f"few queries Nq={Nq} Nk={Nk} d={d} H={H} causal={causal}")
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq,Nk,H", [(1, 16384, 8), (1, 1, 3), (1, 129, 1), (3, 1000, 5), (8, 4097, 8), (5, 300, 16), (2, 20000, 2), (8, 8, 4)])
+def test_key_split_calls_equal_the_sequential_walk(ifa, Nq, Nk, H, d):
+    # The key-split path forms P on the grid of the running maximum of the sequential walk (it knows every block's
+    # maximum before it forms any P), so it differs from the one-workgroup-per-head kernel only by the order of the
+    # fp32 additions of lines 12-13: a few ulp of O, far inside the parity bar.  Checked against that kernel (tight)
+    # and against the oracle (the strict bar), with canary rows behind the output and a workspace of exactly the size
+    # the library asks for, poisoned with NaN (nothing may be read before it is written).
+    for causal in (False, True):
+        rng = np.random.default_rng(Nq * 7 + Nk + d + H + int(causal))
+        Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, max(Nq, Nk), d, score_sigma=2.0)
+        Qq, sQ = np.ascontiguousarray(Qq[:, :Nq]), np.ascontiguousarray(sQ[:, :Nq])
+        Kq, Vq, sK = np.ascontiguousarray(Kq[:, :Nk]), np.ascontiguousarray(Vq[:, :Nk]), np.ascontiguousarray(sK[:, :Nk])
+        args = (dev(Qq[None]), dev(Kq[None]), dev(Vq[None]), dev(sQ[None]), dev(sK[None]), dev(sV[None]))
+        seq = ifa.int_flash_attn_fwd(*args, causal=causal, out_dtype=torch.float32)
+        guard = 64
+        Obuf = torch.full((H * Nq + guard, d), 12345.0, dtype=torch.float32, device="cuda")
+        O = Obuf[:H * Nq].view(1, H, Nq, d)
+        need = ifa.splitk_workspace_bytes(1, H, Nq, Nk, d)
+        ws = torch.full((need // 4 + guard,), float("nan"), dtype=torch.float32, device="cuda")
+        ifa.int_flash_attn_fwd_splitk(*args, causal=causal, out=O, workspace=ws[:need // 4].view(torch.uint8))
+        torch.cuda.synchronize()
+        assert bool((Obuf[H * Nq:] == 12345.0).all()) and bool(torch.isnan(ws[need // 4:]).all())
+        scale = float(seq.abs().max())
+        diff = float((O - seq).abs().max())
+        assert diff <= 4e-6 * scale, (Nq, Nk, H, d, causal, diff, scale)
+        check_against_oracle(ifa, O.cpu().numpy().reshape(-1, d), Qq, Kq, Vq, sQ, sK, sV, causal,
+                             label=f"key split Nq={Nq} Nk={Nk} d={d} H={H} causal={causal}")
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float16, torch.bfloat16])
+def test_key_split_two_byte_outputs(ifa, out_dtype):
+    # the two-byte outputs are the fp32 result rounded to nearest even, as everywhere else in the library
+    H, Nq, Nk, d = 8, 4, 3000, 128
+    rng = np.random.default_rng(99)
+    Qq, Kq, Vq, sQ, sK, sV = random_int8_problem(rng, H, Nk, d, score_sigma=2.0)
+    Qq, sQ = np.ascontiguousarray(Qq[:, :Nq]), np.ascontiguousarray(sQ[:, :Nq])
+    args = (dev(Qq[None]), dev(Kq[None]), dev(Vq[None]), dev(sQ[None]), dev(sK[None]), dev(sV[None]))
+    o32 = ifa.int_flash_attn_fwd_splitk(*args, causal=True, out_dtype=torch.float32)
+    o16 = ifa.int_flash_attn_fwd_splitk(*args, causal=True, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(o16, o32.to(out_dtype))
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_random_int8_grid_inputs_wide_scores(ifa, causal):
     # int8 values over the whole range with score spreads from flat to nearly one-hot rows
