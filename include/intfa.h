@@ -32,7 +32,7 @@ typedef enum {
     IFA_ERR_DTYPE = -3,       /* dtype enum out of range                                      */
     IFA_ERR_UNSUPPORTED = -4, /* valid but not built: d, N granularity, misaligned pointer    */
     IFA_ERR_HIP = -5,         /* the HIP runtime refused the launch (hipGetLastError != 0)    */
-    IFA_ERR_WORKSPACE = -6    /* the shape needs more workspace than the caller gave          */
+    IFA_ERR_WORKSPACE = -6    /* the shape needs more workspace than given / than is built in  */
 } ifa_status;
 
 /* Human-readable name of a status code (static storage, never null). */
@@ -162,6 +162,24 @@ int int_flash_attn_fwd_splitk(const signed char *Q_i8, const signed char *K_i8, 
                               const float *s_Q, const float *s_K, const float *s_V,
                               int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype,
                               void *workspace, long workspace_bytes, void *hip_stream);
+
+/*
+ * int_flash_attn_fwd_splitk for callers that cannot allocate device memory and have no buffer to lend: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same results; the workspace is an array built into the library's device image
+ * (ifa_static_workspace_bytes() bytes, 16 MiB, held by every GPU the library runs on until the process ends).  The
+ * call allocates nothing and frees nothing.  A shape with ifa_splitk_workspace_bytes(...) beyond that size is refused
+ * with IFA_ERR_WORKSPACE before any launch (16 MiB hold, e.g., B*H = 128 heads of 16384 keys at Nq = 1).
+ * Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams, two threads) race
+ * on it and must be serialized by the caller.  Nothing in it needs clearing between calls: every word a call reads
+ * it has written before.
+ */
+long ifa_static_workspace_bytes(void);
+
+int int_flash_attn_fwd_splitk_static(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                     const float *s_Q, const float *s_K, const float *s_V,
+                                     int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype,
+                                     void *hip_stream);
 
 /*
  * Per-block quantization of V -- the scheme the paper names as its next step (Section 3.2, footnote;

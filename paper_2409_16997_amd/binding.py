@@ -25,6 +25,8 @@ SIGNATURES = {
     "int_flash_attn_fwd_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
     "ifa_splitk_workspace_bytes": (_l, [_i] * 5),
     "int_flash_attn_fwd_splitk": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp, _l, _vp]),
+    "ifa_static_workspace_bytes": (_l, []),
+    "int_flash_attn_fwd_splitk_static": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),
     "quantize_blockwise": (_i, [_vp, _i, _l, _l, _i, _i, _vp, _vp, _vp]),
     "int_flash_attn_fwd_vblock": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
     "int_flash_attn_fwd_vblock_rect": (_i, [_vp] * 6 + [_i] * 6 + [_vp, _i, _vp]),

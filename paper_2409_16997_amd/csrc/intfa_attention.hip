@@ -48,6 +48,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <mutex>
 #include <type_traits>
 
 #include "intfa.h"
@@ -1228,7 +1229,7 @@ extern "C" const char *ifa_status_str(int status) {
     case IFA_ERR_DTYPE: return "IFA_ERR_DTYPE: unknown dtype";
     case IFA_ERR_UNSUPPORTED: return "IFA_ERR_UNSUPPORTED: shape, granularity or alignment not supported";
     case IFA_ERR_HIP: return "IFA_ERR_HIP: HIP launch failed";
-    case IFA_ERR_WORKSPACE: return "IFA_ERR_WORKSPACE: the shape needs more workspace than was given ";
+    case IFA_ERR_WORKSPACE: return "IFA_ERR_WORKSPACE: the shape needs more workspace than was given (or than the static workspace holds)";
     default: return "unknown ifa_status";
     }
 }
@@ -1290,6 +1291,46 @@ extern "C" int int_flash_attn_fwd_splitk(const signed char *Q_i8, const signed c
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return IFA_ERR_UNSUPPORTED;
     if (workspace_bytes < ifa_splitk_workspace_bytes(B, H, Nq, Nk, d)) return IFA_ERR_WORKSPACE;
     return splitk_dispatch(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, Nq, Nk, d, causal, O, o_dtype, static_cast<float *>(workspace),
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- the key-split path for callers that cannot allocate -------------------------------------------------------
+// The same three launches with the workspace in a file-scope device array instead of a buffer of the caller's.  In
+// host code the array's name is only a stand-in for the symbol: the device address is asked for once per device
+// (hipGetSymbolAddress, with that device current) and kept; every GPU holds its own copy of the array.
+constexpr long STATIC_WORKSPACE_BYTES = 16L << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device, or null
+void *static_workspace() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" long ifa_static_workspace_bytes(void) { return STATIC_WORKSPACE_BYTES; }
+
+extern "C" int int_flash_attn_fwd_splitk_static(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
+                                                const float *s_Q, const float *s_K, const float *s_V, int B, int H, int Nq,
+                                                int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream) {
+    const int rc = splitk_args(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, Nq, Nk, d, causal, O, o_dtype);
+    if (rc != IFA_OK) return rc;
+    if (ifa_splitk_workspace_bytes(B, H, Nq, Nk, d) > STATIC_WORKSPACE_BYTES) return IFA_ERR_WORKSPACE;
+    void *ws = static_workspace();
+    if (!ws) return IFA_ERR_HIP;
+    return splitk_dispatch(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, B, H, Nq, Nk, d, causal, O, o_dtype, static_cast<float *>(ws),
                            static_cast<hipStream_t>(hip_stream));
 }
 
