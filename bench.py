@@ -40,6 +40,81 @@ def read_traffic(workload):
         return None
 
 
+def decode_bench(args, torch, ifa):
+    """One decode-shaped call: Nq queries per head (the last Nq positions) against Nk keys, causal.  A step is the
+    attention call alone: in a decode loop K and V sit quantized in the cache and only the new tokens are quantized."""
+    B, H, Nq, Nk, d = (int(x) for x in args.decode.split(","))
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(20240916)
+    K = torch.randn((B, H, Nk, d), device=dev, generator=g, dtype=torch.float16)
+    V = torch.randn((B, H, Nk, d), device=dev, generator=g, dtype=torch.float16)
+    Q = torch.randn((B, H, Nq, d), device=dev, generator=g, dtype=torch.float16)
+    fold = 1.0 / math.sqrt(d)
+    Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
+    Kq, sK = ifa.quantize_tokenwise(K)
+    Vq, sV = ifa.quantize_headwise(V)
+    O1 = torch.empty((B, H, Nq, d), dtype=torch.float16, device=dev)
+    O2 = torch.empty_like(O1)
+    need = ifa.splitk_workspace_bytes(B, H, Nq, Nk, d)
+    if need == 0:
+        sys.exit("bench.py --decode: the key-split path takes at most 8 queries per head and d in {64, 128}")
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    calls = {"one_workgroup_per_head": lambda: ifa.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal=True, out=O1),
+             "key_split": lambda: ifa.int_flash_attn_fwd_splitk(Qq, Kq, Vq, sQ, sK, sV, causal=True, out=O2, workspace=ws)}
+    ms = {}
+    for name, fn in calls.items():
+        t_pre = time.perf_counter()
+        while time.perf_counter() - t_pre < PREWARM_S:
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        ms[name] = (time.perf_counter() - t0) * 1e3 / args.steps
+    heads = B * H
+    algo_bytes = heads * (2 * Nk * d + 4 * Nk + Nq * d + 4 * Nq + 2 * Nq * d) + 4 * heads   # K, V, s_K; Q, s_Q, O; s_V
+    ops = 4.0 * heads * d * sum(Nk - Nq + i + 1 for i in range(Nq))
+    result = {"metric": "decode_attention_kv_stream", "value": round(algo_bytes / (ms["key_split"] * 1e-3) / 1e9, 1), "unit": "GB/s",
+              "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms["key_split"], 4),
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+              "config": {"workload": f"decode: B={B} H={H} Nq={Nq} Nk={Nk} d={d} causal, N(0,1) fp16 activations quantized beforehand; "
+                                     "step = one attention call on the quantized cache", "workspace_bytes": need, "int8_ops_per_step": ops},
+              "ms_one_workgroup_per_head": round(ms["one_workgroup_per_head"], 4),
+              "roofline": {"bound": "hbm", "kernel": "splitk_scores_kernel + splitk_pv_kernel + splitk_combine_kernel (one call)",
+                           "achieved": round(algo_bytes / (ms["key_split"] * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                           "frac": round(algo_bytes / (ms["key_split"] * 1e-3) / 8e12, 4), "traffic": None,
+                           "note": "algorithmic bytes: K, V int8 and s_K read once, Q, s_Q, s_V read, O written; the scores that pass "
+                                   "through the workspace (8 Nq bytes per key) are traffic of the method's implementation, not counted"}}
+    if not args.no_cpu_baseline:
+        import oracle
+        n_heads = min(heads, 4)
+        t_cpu, worst = 0.0, 0.0
+        for h in range(n_heads):
+            b, hh = divmod(h, H)
+            q, k, v = (t[b, hh].float().cpu().numpy()[None] for t in (Q, K, V))
+            t2 = time.perf_counter()
+            oQ, osQ = oracle.quantize_tokenwise(q)
+            oK, osK = oracle.quantize_tokenwise(k)
+            oV, osV = oracle.quantize_headwise(v)
+            osQ = (osQ * np.float32(fold)).astype(np.float32)
+            t_cpu += time.perf_counter() - t2            # (the cache is quantized once, not per step: not part of the step)
+            t2 = time.perf_counter()
+            res = oracle.compare_up_to_ties(O2[b, hh].float().cpu().numpy(), oQ, oK, oV, osQ, osK, osV, True, ifa.block_cols(d, True),
+                                            tol=1e-3 + 2.0 ** -10)
+            t_cpu += time.perf_counter() - t2
+            worst = max(worst, float(res["err"].max() / res["scale"]))
+        result["cpu_baseline"] = {"value": round(n_heads * algo_bytes / heads / t_cpu / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle", "seconds": round(t_cpu, 2), "sample": f"{n_heads} of {heads} heads, quantize + Algorithm 1"}
+        result["parity_max_rel_err_vs_oracle"] = worst
+        result["max_rel_diff_between_the_two_paths"] = float((O1.float() - O2.float()).abs().max() / O1.float().abs().max())
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +128,10 @@ def main():
                          "vblock: Algorithm 1 with one V scale per key block (the paper's stated next step)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
+    ap.add_argument("--decode", default=None, metavar="B,H,Nq,Nk,d",
+                    help="not the headline benchmark: time one decode-shaped attention call (Nq <= 8 queries per head against Nk "
+                         "keys, causal) through the one-workgroup-per-head kernel and through the key-split path, K and V already "
+                         "quantized and resident in HBM; prints one JSON line with an HBM roofline for the key-split call")
     ap.add_argument("--zero-operands", action="store_true",
                     help="profiling aid, not a benchmark: all-zero activations, i.e. the same instruction stream on operands "
                          "that toggle no bits -- the difference to the real run is what the clock the chip settles at under "
@@ -72,6 +151,8 @@ def main():
     ifa.lib()                                   # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.decode:
+        return decode_bench(args, torch, ifa)
     dev = torch.device("cuda:0")
     w = workloads.WORKLOADS[args.workload]
     sh = (w.B, w.H, w.N, w.d)

@@ -34,3 +34,18 @@ def test_bench_prints_one_json_line_with_the_contract_fields(variant):
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     assert d["parity_max_rel_err_vs_oracle"] <= 1e-3 + 2.0 ** -10      # fp16 output rounding on top of the parity bar
+
+
+@pytest.mark.timeout(300)
+def test_bench_decode_mode_prints_an_hbm_roofline_line():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--decode", "1,8,3,3000,128", "--steps", "5", "--warmup", "2"],
+                       capture_output=True, text=True, timeout=250)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["metric"] == "decode_attention_kv_stream" and d["unit"] == "GB/s" and d["n_gpus"] == 1 and d["value"] > 0
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and 0 < rf["frac"] < 1 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert d["cpu_baseline"]["kind"] == "oracle" and d["parity_max_rel_err_vs_oracle"] <= 1e-3 + 2.0 ** -10
+    assert d["max_rel_diff_between_the_two_paths"] <= 2.0 ** -9
