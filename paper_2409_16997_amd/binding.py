@@ -187,7 +187,8 @@ def splitk_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int) -> int:
 def int_flash_attn_fwd_splitk(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None, workspace=None):
     """Algorithm 1 for at most 8 queries per head against many keys (a decode step), the key axis split over the
     whole chip: same shapes and mask convention as int_flash_attn_fwd.  `workspace`: a uint8 device tensor of at least
-    splitk_workspace_bytes(...) bytes (allocated here if not given)."""
+    splitk_workspace_bytes(...) bytes (allocated here if not given), or the string "static": the library's built-in
+    16 MiB workspace (no allocation at all; calls that overlap on one GPU must not share it)."""
     import torch
     B, H, N, d = Q_i8.shape
     Nk = K_i8.shape[2]
@@ -199,6 +200,14 @@ def int_flash_attn_fwd_splitk(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out
     need = splitk_workspace_bytes(B, H, N, Nk, d)
     if need == 0:
         raise IntfaError("int_flash_attn_fwd_splitk: shape not supported (at most 8 queries per head, d in {64, 128})")
+    if isinstance(workspace, str):
+        if workspace != "static":
+            raise IntfaError("workspace: a uint8 device tensor, None or 'static'")
+        code = lib().int_flash_attn_fwd_splitk_static(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),
+                                                      _dev(s_Q, torch.float32), _dev(s_K, torch.float32), _dev(s_V, torch.float32),
+                                                      B, H, N, Nk, d, int(bool(causal)), _dev(out), _dtype_enum(out), _stream())
+        _check(code, "int_flash_attn_fwd_splitk_static")
+        return out
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q_i8.device)
     code = lib().int_flash_attn_fwd_splitk(_dev(Q_i8, torch.int8), _dev(K_i8, torch.int8), _dev(V_i8, torch.int8),

@@ -388,6 +388,8 @@ __global__ __launch_bounds__(256 * W) void layers_kernel(LayerIters li, WaveRec 
 //   STRUCT 4: the kernel's S phase (as STRUCT 0), then as STRUCT 2: P tile 0 | M2 with the next tile's exps | V3
 //   STRUCT 5: as 2 with two accumulators at a time: P tile 0 | 4 x (2 MFMA (d tiles 0, 1) with 16 (fma, exp, cvt_pk)
 //             of the next tile) | 8 MFMA (d tiles 2, 3) | V3
+//   STRUCT 6: M1 is only the second half of the S phase (8 MFMA); after V1 one run of 24 MFMAs -- the first half of the
+//             NEXT block's S phase, then M2 -- with the (fma, exp, cvt_pk) of P behind the first 20 of them, 3.2 per MFMA
 //   PRIO 0: no s_setprio; 1: priority 3 while a section issues MFMAs, 0 otherwise; 2: the reverse; 3: priority 3 in
 //   M2 only; 4: in M1 only; 5: as 1 with priority 1 instead of 3
 //   LDS_KB: static LDS per workgroup: 96 admits one workgroup per CU, 64 two (then W = 1 and the grid has 2 per CU:
@@ -469,7 +471,7 @@ __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec,
             }
             if (STRUCT != 4) prio_m(1);
 #pragma unroll
-            for (int u = 0; u < (STRUCT == 4 ? 0 : 16); ++u) {
+            for (int u = 0; u < (STRUCT == 4 ? 0 : STRUCT == 6 ? 8 : 16); ++u) {
                 mfma(r.c[(u >> 2) & 3], r.a, r.b);
                 if (STRUCT == 3) {
 #pragma unroll
@@ -518,6 +520,25 @@ __global__ __launch_bounds__(256 * W) void phase_kernel(int iters, WaveRec *rec,
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) mfma(r.c[2 + (u >> 2)], r.a, r.b);
+                prio_v();
+            } else if (STRUCT == 6) {
+                // 8 MFMAs of the NEXT block's S phase, then the 16 of this block's O phase: one run of 24 MFMAs; the 64
+                // (fma, exp, cvt_pk) of P go behind the first 20 of them, 3.2 per MFMA (P tile t is complete before MFMA 8 + 4 t)
+                prio_m(2);
+#pragma unroll
+                for (int u = 0; u < 24; ++u) {
+                    mfma(r.c[(u >> 2) & 3], r.a, r.b);
+                    if (u < 20) {
+                        const int lo = (u * 16 + 4) / 5, hi = ((u + 1) * 16 + 4) / 5;
+#pragma unroll
+                        for (int e = lo; e < hi; ++e) vop<FMA3>(r.e[e & 15], r.y, r.z);
+#pragma unroll
+                        for (int e = lo; e < hi; ++e) vop<EXP>(r.e[e & 15], r.y, r.z);
+#pragma unroll
+                        for (int e = lo; e < hi; ++e) vop<CVTPK>(r.x[24 + (e & 3)], r.e[(e + 8) & 15], r.z);
+                        if (u < 16) vop<SADU8>(r.x[28 + (u & 3)], r.y, r.z);
+                    }
+                }
                 prio_v();
             } else if (STRUCT == 2 || STRUCT == 4) {
                 p_tile(0, 2);
@@ -778,7 +799,8 @@ int main(int argc, char **argv) {
         const int bit = 1500;
         static const char *STRUCT_NAME[] = {"kernel order (MFMA groups of 4, fp32 work between)", "sections M1 | V1 | V2 | M2 | V3",
                                             "sections, exps of the next P tile inside M2", "V1 spread over M1, V3 over M2, V2 apart",
-                                            "kernel-order S phase, then exps inside M2", "exps inside M2, two accumulators at a time"};
+                                            "kernel-order S phase, then exps inside M2", "exps inside M2, two accumulators at a time",
+                                            "half of the next S phase in front of M2, exps under both"};
         static const char *PRIO_NAME[] = {"no setprio", "prio 3 in MFMA sections", "prio 3 in vector sections", "prio 3 in M2 only", "prio 3 in M1 only", "prio 1 in MFMA sections"};
         auto phase_line = [&](int st, int pr, int W, const Result &r) {
             const double mhz = r.wall > 0 ? r.cyc / r.wall * 100.0 : 0.0;
@@ -804,6 +826,7 @@ int main(int argc, char **argv) {
         PHASE(2, 3, 2) PHASE(2, 4, 2) PHASE(2, 5, 2)
         PHASE(4, 0, 2) PHASE(4, 1, 2) PHASE(4, 3, 2)
         PHASE(5, 0, 2) PHASE(5, 1, 2) PHASE(5, 3, 2)
+        PHASE(6, 0, 2) PHASE(6, 1, 2) PHASE(6, 3, 2)
         printf("   one 8-wavefront workgroup, one barrier per block: same point for all wavefronts / wavefronts 4-7 one section ahead of it (in front of V3) / half a block ahead (in front of M2):\n");
 #define PHASESTAG(ST, PR, SG)                                                                                                    \
     {                                                                                                                           \
@@ -823,7 +846,7 @@ int main(int argc, char **argv) {
         r2.ms = r.ms;                                                                                                           \
         phase_line(ST, PR, 2, r2);                                                                                              \
     }
-        PHASE2WG(0, 0) PHASE2WG(2, 0) PHASE2WG(2, 1) PHASE2WG(2, 3) PHASE2WG(4, 1) PHASE2WG(4, 3) PHASE2WG(5, 1)
+        PHASE2WG(0, 0) PHASE2WG(2, 0) PHASE2WG(2, 1) PHASE2WG(2, 3) PHASE2WG(4, 1) PHASE2WG(4, 3) PHASE2WG(5, 1) PHASE2WG(6, 1) PHASE2WG(6, 3)
     }
     if (want("block")) {
         printf("\n== block: skeleton of one key block of the attention kernel per iteration (32 MFMA = 1024 cycles at the datasheet rate)\n");
