@@ -57,7 +57,7 @@ def decode_bench(args, torch, ifa):
     O2 = torch.empty_like(O1)
     need = ifa.splitk_workspace_bytes(B, H, Nq, Nk, d)
     if need == 0:
-        sys.exit("bench.py --decode: the key-split path takes at most 8 queries per head and d in {64, 128}")
+        sys.exit("bench.py --decode: the key-split path takes at most 32 queries per head and d in {64, 128}")
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     calls = {"one_workgroup_per_head": lambda: ifa.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal=True, out=O1),
              "key_split": lambda: ifa.int_flash_attn_fwd_splitk(Qq, Kq, Vq, sQ, sK, sV, causal=True, out=O2, workspace=ws)}
@@ -129,7 +129,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the MRE columns")
     ap.add_argument("--attn-only", action="store_true", help="time only the fused kernel (profiling aid)")
     ap.add_argument("--decode", default=None, metavar="B,H,Nq,Nk,d",
-                    help="not the headline benchmark: time one decode-shaped attention call (Nq <= 8 queries per head against Nk "
+                    help="not the headline benchmark: time one decode-shaped attention call (Nq <= 32 queries per head against Nk "
                          "keys, causal) through the one-workgroup-per-head kernel and through the key-split path, K and V already "
                          "quantized and resident in HBM; prints one JSON line with an HBM roofline for the key-split call")
     ap.add_argument("--zero-operands", action="store_true",

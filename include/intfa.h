@@ -144,13 +144,16 @@ int int_flash_attn_fwd_rect(const signed char *Q_i8, const signed char *K_i8, co
                             int B, int H, int Nq, int Nk, int d, int causal, void *O, int o_dtype, void *hip_stream);
 
 /*
- * Algorithm 1 for a FEW queries per head against many keys (a decode step, a few speculative tokens), with the key
- * axis of every head split over the whole chip.  Shapes, mask rule and error rules of int_flash_attn_fwd_rect, with
- * Nq <= 8 (else IFA_ERR_UNSUPPORTED).  Lines 9-10 run first for every key block (the scaled scores and the block
- * maxima go to the workspace), so that each part of the key axis forms P on the grid of the running maximum the
- * sequential walk of Algorithm 1 would have at that block: P and the int32 P V are those of int_flash_attn_fwd_rect
- * bit for bit, and O differs from its result only by the order of the fp32 additions of lines 12-13 (the partial
- * (m, l, O) of the parts are merged with e^{m_part - m}, once per part instead of once per block).
+ * Algorithm 1 for a FEW queries per head against many keys (a decode step, a few speculative tokens, a short chunk),
+ * with the key axis of every head split over the whole chip.  Shapes, mask rule and error rules of
+ * int_flash_attn_fwd_rect, with Nq <= 32 (else IFA_ERR_UNSUPPORTED).  Lines 9-10 run first for every key block (the
+ * block maxima go to the workspace; for Nq <= 8 the scaled scores too, for 9 <= Nq <= 32 the second pass computes
+ * them again from K), so that each part of the key axis forms P on the grid of the running maximum the sequential
+ * walk of Algorithm 1 would have at that block: P and the int32 P V are those of int_flash_attn_fwd_rect bit for bit,
+ * and O differs from its result only by the order of the fp32 additions of lines 12-13 (the partial (m, l, O) of the
+ * parts are merged with e^{m_part - m}, once per part instead of once per block).  With 9 <= Nq <= 32 and 96 heads
+ * or more the split does not pay (K would be read twice by a chip that is already full) and the call runs the kernel
+ * of int_flash_attn_fwd_rect.
  *   workspace         device memory, 256-byte aligned, at least ifa_splitk_workspace_bytes(B, H, Nq, Nk, d) bytes
  *                     (else IFA_ERR_WORKSPACE); owned by the caller, contents undefined before and after, must not be
  *                     shared by calls that may overlap.  Three kernel launches on hip_stream, nothing is allocated.

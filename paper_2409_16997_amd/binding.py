@@ -185,7 +185,7 @@ def splitk_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int) -> int:
 
 
 def int_flash_attn_fwd_splitk(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out_dtype=None, out=None, workspace=None):
-    """Algorithm 1 for at most 8 queries per head against many keys (a decode step), the key axis split over the
+    """Algorithm 1 for at most 32 queries per head against many keys (a decode step, a short chunk), the key axis split over the
     whole chip: same shapes and mask convention as int_flash_attn_fwd.  `workspace`: a uint8 device tensor of at least
     splitk_workspace_bytes(...) bytes (allocated here if not given), or the string "static": the library's built-in
     16 MiB workspace (no allocation at all; calls that overlap on one GPU must not share it)."""
@@ -199,7 +199,7 @@ def int_flash_attn_fwd_splitk(Q_i8, K_i8, V_i8, s_Q, s_K, s_V, causal=False, out
         out = torch.empty((B, H, N, d), dtype=out_dtype or torch.float16, device=Q_i8.device)
     need = splitk_workspace_bytes(B, H, N, Nk, d)
     if need == 0:
-        raise IntfaError("int_flash_attn_fwd_splitk: shape not supported (at most 8 queries per head, d in {64, 128})")
+        raise IntfaError("int_flash_attn_fwd_splitk: shape not supported (at most 32 queries per head, d in {64, 128})")
     if isinstance(workspace, str):
         if workspace != "static":
             raise IntfaError("workspace: a uint8 device tensor, None or 'static'")

@@ -770,7 +770,9 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
 // in the loops; a wavefront's ring of staged blocks is ordered by its own counted s_waitcnt alone.  The four
 // wavefronts meet once, after their loops: their minima (pass 1) and their partial (l, O) at the common m (pass 2)
 // are combined through LDS.
-constexpr int SPLIT_MAX_Q = 8;       // queries per head (a decode step, a few speculative tokens)
+constexpr int SPLIT_MAX_Q = 8;       // queries per head up to which the scores go through memory (a decode step, a few speculative tokens)
+constexpr int SPLIT_MAX_Q_RECOMPUTE = 32;   // ... and up to which the second pass recomputes them from K instead (one column tile)
+constexpr int SPLIT_RECOMPUTE_MAX_HEADS = 96;   // ... as long as there are fewer heads than this
 constexpr int SPLIT_NSTAGE_K = 4;    // pass 1: ring of K blocks, filled three ahead
 constexpr int SPLIT_NSTAGE_V = 3;    // pass 2: ring of V blocks, filled two ahead
 constexpr bool SPLIT_NT = true;      // staging copies carry the non-temporal hint: every byte is read once (measured +7 % at 537 MB of K and V)
@@ -778,7 +780,7 @@ constexpr bool SPLIT_NT = true;      // staging copies carry the non-temporal hi
 template <int D> struct SmemSplitK {
     alignas(4096) int8_t k[SPLIT_NSTAGE_K][BC * D];
     alignas(256) float sk[SPLIT_NSTAGE_K][4][64];             // per wavefront: the 32 s_K of its key tile (+ 32 unused)
-    alignas(16) float red[4][SPLIT_MAX_Q];
+    alignas(16) float red[4][SPLIT_MAX_Q_RECOMPUTE];
 };
 template <int D> struct SmemSplitV {
     alignas(4096) int8_t v[SPLIT_NSTAGE_V][BC * D];
@@ -790,36 +792,52 @@ template <int D> struct SmemSplitV {
 static_assert(2 * sizeof(SmemSplitK<128>) <= 160 * 1024 && 2 * sizeof(SmemSplitV<128>) <= 160 * 1024, "two workgroups per CU");
 static_assert(offsetof(SmemSplitV<64>, v) % 4096 == 0 && (BC * 64) % 4096 == 0, "tile bases");
 
-// Layout of the workspace (fp32 words), shared by the host code and the kernels:
-//   scores  [heads, T_c, 4 tiles, Nq, 32]     a of line 9 (masked keys: +inf)
-//   tmin    [heads, T_c, SPLIT_MAX_Q, 4]      minimum of a per (block, query, tile); queries >= Nq unused
-//   cmin    [heads, SPLIT_MAX_Q, nchunks]     minimum of a per (run of blocks, query)
-//   part_o  [heads, nchunks, Nq, d]           one partial per run of blocks
-//   part_ml [heads, nchunks, Nq, 2]           m (log2 units) and l of the partial
+// Second pass for 9 .. 32 queries per head: the scores would be as many bytes as K and V, so they are not stored;
+// the pass streams K once more and recomputes line 9 (same MFMA chain, same scaling: the same numbers).
+template <int D> struct SmemSplitKV {
+    alignas(4096) int8_t k[SPLIT_NSTAGE_V][BC * D];
+    alignas(4096) int8_t v[SPLIT_NSTAGE_V][BC * D];
+    alignas(256) float sk[SPLIT_NSTAGE_V][4][64];
+    alignas(1024) float tmin[SPLIT_NSTAGE_V][4][256];           // per wavefront: the block's [query][tile] minima (512 B, + 512 unused)
+    alignas(16) float pre[SPLIT_MAX_Q_RECOMPUTE];
+};
+static_assert(sizeof(SmemSplitKV<128>) <= 160 * 1024, "LDS budget");
+
+// Layout of the workspace (fp32 words), shared by the host code and the kernels (MAXQ = 8 or 32, by Nq):
+//   scores  [heads, T_c, 4 tiles, Nq, 32]     a of line 9 (masked keys: +inf); Nq <= 8 only
+//   tmin    [heads, T_c, MAXQ, 4]             minimum of a per (block, query, tile); queries >= Nq unused
+//   cmin    [heads, MAXQ, nchunks]            minimum of a per (run of blocks, query)
+//   part_o  [heads, parts, Nq, d]             one partial per run of blocks
+//   part_ml [heads, parts, Nq, 2]             m (log2 units) and l of the partial
 struct SplitPlan {
-    int cb, nchunks, T_c;
+    int cb, nchunks, T_c, maxq, parts;
+    bool store;
     long off_tmin, off_cmin, off_part_o, off_part_ml, words;
 };
 inline SplitPlan split_plan(long heads, int Nq, int Nk, int d) {
     SplitPlan p;
     p.T_c = (Nk + BC - 1) / BC;
+    p.store = Nq <= SPLIT_MAX_Q;
+    p.maxq = p.store ? SPLIT_MAX_Q : SPLIT_MAX_Q_RECOMPUTE;
     long want = 1024 / heads;                    // about four workgroups per CU over the chip
     if (want < 1) want = 1;
     long cb = (p.T_c + want - 1) / want;
-    if (cb < 2) cb = 2;
+    const long cb_min = p.store ? 2 : 4;         // a run's partial (Nq x d floats) must stay small next to its K and V
+    if (cb < cb_min) cb = cb_min;
     if (cb > p.T_c) cb = p.T_c;
     p.cb = static_cast<int>(cb);
     p.nchunks = (p.T_c + p.cb - 1) / p.cb;       // no run is empty
+    p.parts = p.nchunks;
     auto up = [](long w) { return (w + 63) & ~63L; };            // 256-byte granules
-    p.off_tmin = up(heads * p.T_c * 4 * Nq * 32);
-    p.off_cmin = p.off_tmin + up(heads * p.T_c * SPLIT_MAX_Q * 4);
-    p.off_part_o = p.off_cmin + up(heads * SPLIT_MAX_Q * p.nchunks);
-    p.off_part_ml = p.off_part_o + up(heads * p.nchunks * Nq * d);
-    p.words = p.off_part_ml + up(heads * p.nchunks * Nq * 2);
+    p.off_tmin = p.store ? up(heads * p.T_c * 4 * Nq * 32) : 0;
+    p.off_cmin = p.off_tmin + up(heads * p.T_c * p.maxq * 4);
+    p.off_part_o = p.off_cmin + up(heads * p.maxq * p.nchunks);
+    p.off_part_ml = p.off_part_o + up(heads * p.parts * Nq * d);
+    p.words = p.off_part_ml + up(heads * p.parts * Nq * 2);
     return p;
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, int MAXQ, bool STORE>
 __global__ __launch_bounds__(THREADS, 2) void splitk_scores_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const float *__restrict__ sK, int Nq, int Nk, int cb,
     int nchunks, float *__restrict__ scores, float *__restrict__ tminG, float *__restrict__ cminG) {
@@ -903,18 +921,20 @@ __global__ __launch_bounds__(THREADS, 2) void splitk_scores_kernel(
         tmin = pair_min(tmin);
         wmin = fminf(wmin, tmin);
         if (r < Nq) {
-            float *dst = scores + (((static_cast<long>(head) * T_c + jb) * 4 + wave) * Nq + r) * 32 + 4 * g;
+            if (STORE) {
+                float *dst = scores + (((static_cast<long>(head) * T_c + jb) * 4 + wave) * Nq + r) * 32 + 4 * g;
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) *reinterpret_cast<v4f *>(dst + 8 * vq) = v4f{a[4 * vq], a[4 * vq + 1], a[4 * vq + 2], a[4 * vq + 3]};
-            if (g == 0) tminG[((static_cast<long>(head) * T_c + jb) * SPLIT_MAX_Q + r) * 4 + wave] = tmin;
+                for (int vq = 0; vq < 4; ++vq) *reinterpret_cast<v4f *>(dst + 8 * vq) = v4f{a[4 * vq], a[4 * vq + 1], a[4 * vq + 2], a[4 * vq + 3]};
+            }
+            if (g == 0) tminG[((static_cast<long>(head) * T_c + jb) * MAXQ + r) * 4 + wave] = tmin;
         }
     }
     wait_all_memory();                                           // requests past the run: nothing of mine stays in flight
     // the run's minimum per query, for the prefix the second pass needs: the only exchange between the wavefronts
-    if (g == 0 && r < SPLIT_MAX_Q) sm.red[wave][r] = wmin;
+    if (g == 0 && r < MAXQ) sm.red[wave][r] = wmin;
     __syncthreads();
     if (wave == 0 && g == 0 && r < Nq)
-        cminG[(static_cast<long>(head) * SPLIT_MAX_Q + r) * nchunks + c] = fminf(fminf(sm.red[0][r], sm.red[1][r]), fminf(sm.red[2][r], sm.red[3][r]));
+        cminG[(static_cast<long>(head) * MAXQ + r) * nchunks + c] = fminf(fminf(sm.red[0][r], sm.red[1][r]), fminf(sm.red[2][r], sm.red[3][r]));
 #endif
 }
 
@@ -1045,6 +1065,162 @@ __global__ __launch_bounds__(THREADS, 2) void splitk_pv_kernel(
 #endif
 }
 
+// Second pass for 9 .. 32 queries per head (see SmemSplitKV): lines 9-13 per key tile with m known beforehand.
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(THREADS, 1) void splitk_pv_recompute_kernel(
+    const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V, const float *__restrict__ sQ,
+    const float *__restrict__ sK, int Nq, int Nk, int cb, int nchunks, const float *__restrict__ tminG,
+    const float *__restrict__ cminG, float *__restrict__ part_o, float *__restrict__ part_ml) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __shared__ SmemSplitKV<D> sm;
+    constexpr int KS = D / 32, DT = D / 32, MAXQ = SPLIT_MAX_Q_RECOMPUTE;
+    constexpr int PER_BLOCK = KS + DT + 2;                       // copy instructions per wavefront and block
+    const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T_c = (Nk + BC - 1) / BC;
+    const int head = blockIdx.x / nchunks, c = blockIdx.x % nchunks;
+    const int jb0 = c * cb, jb1 = min(T_c, jb0 + cb);
+    const int shift = CAUSAL ? Nk - Nq : 0;
+    const int rq = min(r, Nq - 1);
+
+    const BufRsrc rK = make_rsrc(K + static_cast<long>(head) * Nk * D, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rV = make_rsrc(V + static_cast<long>(head) * Nk * D, static_cast<unsigned>(Nk) * D);
+    const BufRsrc rSK = make_rsrc(sK + static_cast<long>(head) * Nk, static_cast<unsigned>(Nk) * 4);
+    const BufRsrc rT = make_rsrc(tminG + static_cast<long>(head) * T_c * MAXQ * 4, static_cast<unsigned>(T_c) * MAXQ * 4 * 4);
+    const lds_ptr kbuf = (lds_ptr)(&sm.k[0][0]);
+    const lds_ptr vbuf = (lds_ptr)(&sm.v[0][0]);
+    const lds_ptr skbuf = (lds_ptr)(&sm.sk[0][0][0]);
+    const lds_ptr tbuf = (lds_ptr)(&sm.tmin[0][0][0]);
+    const LaneOffsets<D> lo(lane, wave);
+    // this wavefront's key tile of K_j and V_j, its 32 s_K, and the block's 128 tile minima (lanes 32-63 repeat 0-31)
+    auto stage_block = [&](int jb) {
+        const int st = (jb - jb0) % SPLIT_NSTAGE_V;
+        const bool real = jb < jb1;
+        const Prefetch pf = {rK, rV, rSK, real ? jb * BC * D : NOWHERE, real ? jb * BC * 4 : NOWHERE,
+                             kbuf + st * BC * D, vbuf + st * BC * D, skbuf + (st * 4 + wave) * 256};
+#pragma unroll
+        for (int i = 0; i < KS; ++i) prefetch_k_piece<D, SPLIT_NT>(pf, lo, wave, i);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) prefetch_v_piece<D, SPLIT_NT>(pf, lo, wave, i);
+        lds_copy4(pf.sk, pf.lsk, 4 * r + 128 * wave, pf.skoff);
+        lds_copy16(rT, tbuf + (st * 4 + wave) * 1024, 16 * r, real ? jb * (MAXQ * 4 * 4) : NOWHERE);
+    };
+    stage_block(jb0);
+    stage_block(jb0 + 1);
+
+    const int8_t *qptr = Q + (static_cast<long>(head) * Nq + rq) * D + 16 * g;
+    v4i qf[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = *reinterpret_cast<const v4i *>(qptr + 32 * kk);
+    float nq2 = sQ[static_cast<long>(head) * Nq + rq] * (-LOG2E * ACC_UNIT);
+    // minimum of a over the runs in front of this one: 8 threads per query
+    float pre = INFINITY;
+    {
+        const int q = tid >> 3;
+        if (q < Nq)
+            for (int cc = tid & 7; cc < c; cc += 8) pre = fminf(pre, cminG[(static_cast<long>(head) * MAXQ + q) * nchunks + cc]);
+#pragma unroll
+        for (int s_ = 4; s_ >= 1; s_ >>= 1) pre = fminf(pre, __shfl_xor(pre, s_));
+        if ((tid & 7) == 0) sm.pre[q] = pre;
+    }
+    // landed BEFORE the loop as far as the compiler is concerned (no wait of its own for them inside the loop)
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+v"(qf[kk]));
+    asm volatile("" : "+v"(nq2));
+    __syncthreads();
+    pre = sm.pre[rq];
+    float m2 = (pre == INFINITY) ? -INFINITY : pre * nq2;        // line 10 over all earlier blocks (no block: line 6)
+    float l = 0.0f, o[DT][16];
+    v16i acc0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        acc0[v] = ACC_START_I;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt][v] = 0.0f;
+    }
+
+    for (int jb = jb0; jb < jb1; ++jb) {
+        const int st = (jb - jb0) % SPLIT_NSTAGE_V, j0 = jb * BC;
+        wait_vmcnt<PER_BLOCK>();                                 // block jb has landed (block jb + 1 may be in flight)
+        stage_block(jb + 2);                                     // into the stage of block jb - 1, which this wavefront has left
+        const lds_ptr ks = kbuf + st * BC * D, vs = vbuf + st * BC * D;
+        // line 9 for key tile `wave`, as in the first pass
+        v4i kop[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) kop[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(ks, lo, kk) + 32 * wave * D);
+        v4f skv[4];
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) skv[vq] = *reinterpret_cast<LDS_AS const v4f *>(skbuf + (st * 4 + wave) * 256 + lo.sk + 32 * vq);
+        v16i sacc = acc0;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) sacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kop[kk], qf[kk], sacc, 0, 0, 0);
+        const int tail = Nk - 1 - j0;
+        const int klimit = CAUSAL ? min(rq + shift - j0, tail) : tail;
+        const bool masked = CAUSAL ? (j0 + BC - 1 > min(shift, Nk - 1)) : (tail < BC - 1);   // wave-uniform
+        // line 10 for the whole block: the four tile minima of this lane's query
+        const v4f t4 = *reinterpret_cast<LDS_AS const v4f *>(tbuf + (st * 4 + wave) * 1024 + rq * 16);
+        const float bmin = fminf(fminf(t4[0], t4[1]), fminf(t4[2], t4[3]));
+        const float m_new = fmaxf(m2, bmin * nq2);
+        const float alpha = __builtin_amdgcn_exp2f(m2 - m_new);
+        const float mm = m_new - LOG2_R_NORM;
+        m2 = m_new;
+        // line 11
+        v4i pw;
+        uint32_t psum = 0;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float av = (ACC_START_F - __int_as_float(sacc[4 * vq + e])) * skv[vq][e];
+                if (masked && (32 * wave + 8 * vq + 4 * g + e > klimit)) av = INFINITY;
+                x[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(av, nq2, -mm));
+            }
+            const uint32_t w = pack_p4(x);
+            psum = __builtin_amdgcn_sad_u8(w, 0u, psum);
+            pw[vq] = static_cast<int>(w);
+        }
+        l = __builtin_fmaf(l, alpha, static_cast<float>(psum));  // line 12 over this lane's keys of this tile
+        // line 13 over the keys of this tile, all d tiles
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const v2i t0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 32 * wave * D));
+            const v2i t1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(reinterpret_cast<LDS_AS v2i *>(v_operand<D>(vs, lo, dt) + 16 * D + 32 * wave * D));
+            const v4i vop = {t0[0], t0[1], t1[0], t1[1]};
+            const v16i pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop, pw, acc0, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[dt][v] = __builtin_fmaf(o[dt][v], alpha, -(ACC_START_F - __int_as_float(pacc[v])));
+        }
+    }
+    wait_all_memory();
+    // The four wavefronts hold partials of the same run at the same m: their sum is the workgroup's partial.  The K
+    // and V rings (contiguous) are free once every wavefront has left the loop; [wavefront][query][d] floats go through them.
+    static_assert(offsetof(SmemSplitKV<D>, v) == sizeof(SmemSplitKV<D>::k) && 4 * MAXQ * D * 4 <= 2 * SPLIT_NSTAGE_V * BC * D, "exchange area");
+    const float lt = l + swap32(l);
+    __syncthreads();
+    float *xo = reinterpret_cast<float *>(&sm.k[0][0]);
+    float *xl = reinterpret_cast<float *>(&sm.sk[0][0][0]);      // [wavefront][query]
+    if (r < Nq) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq)
+                *reinterpret_cast<v4f *>(xo + (wave * MAXQ + r) * D + 32 * dt + 8 * vq + 4 * g) = v4f{o[dt][4 * vq], o[dt][4 * vq + 1], o[dt][4 * vq + 2], o[dt][4 * vq + 3]};
+        if (g == 0) xl[wave * MAXQ + r] = lt;
+    }
+    __syncthreads();
+    const long slot0 = (static_cast<long>(head) * nchunks + c) * Nq;
+    for (int idx = tid; idx < Nq * D; idx += THREADS) {
+        const int q = idx / D, t = idx % D;
+        part_o[(slot0 + q) * D + t] = (xo[(0 * MAXQ + q) * D + t] + xo[(1 * MAXQ + q) * D + t]) + (xo[(2 * MAXQ + q) * D + t] + xo[(3 * MAXQ + q) * D + t]);
+    }
+    if (wave == 0 && g == 0 && r < Nq) {
+        part_ml[2 * (slot0 + r)] = m2;
+        part_ml[2 * (slot0 + r) + 1] = (xl[r] + xl[MAXQ + r]) + (xl[2 * MAXQ + r] + xl[3 * MAXQ + r]);
+    }
+#endif
+}
+
 // Lines 15-17 over the partial results of one (head, query).  256 threads: thread (pg, dq) sums the parts p = pg, pg + PG,
 // ... for output columns 4 dq .. 4 dq + 3 (PG = 1024 / D groups of parts, D / 4 column quads), LDS adds the groups up.
 template <int D, typename OutT>
@@ -1135,10 +1311,18 @@ int launch_splitk(const int8_t *Q, const int8_t *K, const int8_t *V, const float
     const SplitPlan p = split_plan(heads, Nq, Nk, D);
     float *scores = ws, *tmin = ws + p.off_tmin, *cmin = ws + p.off_cmin, *part_o = ws + p.off_part_o, *part_ml = ws + p.off_part_ml;
     const dim3 grid(static_cast<unsigned>(static_cast<long>(heads) * p.nchunks));
-    hipLaunchKernelGGL((splitk_scores_kernel<D, CAUSAL>), grid, dim3(THREADS), 0, st, Q, K, sK, Nq, Nk, p.cb, p.nchunks, scores, tmin, cmin);
-    hipLaunchKernelGGL((splitk_pv_kernel<D>), grid, dim3(THREADS), 0, st, V, sQ, Nq, Nk, p.cb, p.nchunks, scores, tmin, cmin, part_o, part_ml);
+    if (p.store) {
+        hipLaunchKernelGGL((splitk_scores_kernel<D, CAUSAL, SPLIT_MAX_Q, true>), grid, dim3(THREADS), 0, st, Q, K, sK, Nq, Nk, p.cb, p.nchunks,
+                           scores, tmin, cmin);
+        hipLaunchKernelGGL((splitk_pv_kernel<D>), grid, dim3(THREADS), 0, st, V, sQ, Nq, Nk, p.cb, p.nchunks, scores, tmin, cmin, part_o, part_ml);
+    } else {
+        hipLaunchKernelGGL((splitk_scores_kernel<D, CAUSAL, SPLIT_MAX_Q_RECOMPUTE, false>), grid, dim3(THREADS), 0, st, Q, K, sK, Nq, Nk, p.cb,
+                           p.nchunks, scores, tmin, cmin);
+        hipLaunchKernelGGL((splitk_pv_recompute_kernel<D, CAUSAL>), grid, dim3(THREADS), 0, st, Q, K, V, sQ, sK, Nq, Nk, p.cb, p.nchunks, tmin,
+                           cmin, part_o, part_ml);
+    }
     hipLaunchKernelGGL((splitk_combine_kernel<D, OutT>), dim3(static_cast<unsigned>(heads * Nq)), dim3(THREADS), 0, st, part_o, part_ml, sV,
-                       Nq, p.nchunks, static_cast<OutT *>(O));
+                       Nq, p.parts, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
@@ -1161,10 +1345,10 @@ int splitk_args(const signed char *Q_i8, const signed char *K_i8, const signed c
     if (heads > (1L << 40) / Nk / d) return IFA_ERR_SHAPE;
     if (causal && Nk < Nq) return IFA_ERR_UNSUPPORTED;           // a query with no visible key
     if (o_dtype < IFA_F32 || o_dtype > IFA_BF16) return IFA_ERR_DTYPE;
-    if ((d != 64 && d != 128) || Nq > SPLIT_MAX_Q) return IFA_ERR_UNSUPPORTED;
+    if ((d != 64 && d != 128) || Nq > SPLIT_MAX_Q_RECOMPUTE) return IFA_ERR_UNSUPPORTED;
     if (static_cast<long>(Nk) * d > 0x7ff00000L) return IFA_ERR_UNSUPPORTED;      // a head's K (or V) stays below NOWHERE
     const SplitPlan p = split_plan(heads, Nq, Nk, d);
-    if (static_cast<long>(p.T_c) * 4 * Nq * 128 > 0x7ff00000L ||                   // so does a head's scores array
+    if (static_cast<long>(p.T_c) * 4 * p.maxq * 128 > 0x7ff00000L ||               // so do a head's scores and minima arrays
         heads * p.nchunks > 0x7fffffffL || heads * Nq > 0x7fffffffL) return IFA_ERR_UNSUPPORTED;
     if (!ifa_aligned16(Q_i8) || !ifa_aligned16(K_i8) || !ifa_aligned16(V_i8) || !ifa_aligned16(O) ||
         (reinterpret_cast<uintptr_t>(s_Q) & 3) || (reinterpret_cast<uintptr_t>(s_K) & 3) || (reinterpret_cast<uintptr_t>(s_V) & 3))
@@ -1179,6 +1363,15 @@ int splitk_dispatch(const signed char *Q_i8, const signed char *K_i8, const sign
     const int8_t *K = reinterpret_cast<const int8_t *>(K_i8);
     const int8_t *V = reinterpret_cast<const int8_t *>(V_i8);
     const int hd = B * H;
+    // From 9 queries on the second pass reads K again: with many heads the one-workgroup-per-head kernel already fills the
+    // chip and is the faster one (measured: 128 heads x 32 queries x 16384 keys 148 us against 167 us; 32 heads 160 against 73).
+    if (Nq > SPLIT_MAX_Q && hd >= SPLIT_RECOMPUTE_MAX_HEADS) {
+        if (d == 128)
+            return causal ? launch_fwd_dtype<128, true, false>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st)
+                          : launch_fwd_dtype<128, false, false>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st);
+        return causal ? launch_fwd_dtype<64, true, false>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st)
+                      : launch_fwd_dtype<64, false, false>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, st);
+    }
     if (d == 128)
         return causal ? launch_splitk_dtype<128, true>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, ws, st)
                       : launch_splitk_dtype<128, false>(Q, K, V, s_Q, s_K, s_V, hd, Nq, Nk, O, o_dtype, ws, st);
@@ -1275,7 +1468,7 @@ extern "C" int int_flash_attn_fwd(const signed char *Q_i8, const signed char *K_
 }
 
 extern "C" long ifa_splitk_workspace_bytes(int B, int H, int Nq, int Nk, int d) {
-    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || (d != 64 && d != 128) || Nq > SPLIT_MAX_Q) return 0;
+    if (B <= 0 || H <= 0 || Nq <= 0 || Nk <= 0 || (d != 64 && d != 128) || Nq > SPLIT_MAX_Q_RECOMPUTE) return 0;
     const long heads = static_cast<long>(B) * H;
     if (heads > (1L << 40) / Nk / d) return 0;
     return split_plan(heads, Nq, Nk, d).words * 4;

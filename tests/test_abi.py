@@ -94,9 +94,9 @@ def test_argument_validation_happens_on_the_host(L):
     assert rc(p, p, p, p, p, p, 1, 1, 0, 64, 128, 0, p, 1, None) == -2 and rc(p, p, p, p, p, null, 1, 1, 8, 64, 128, 0, p, 1, None) == -1
     sk, wb = L.int_flash_attn_fwd_splitk, L.ifa_splitk_workspace_bytes
     ws = ctypes.c_void_p(0x10000)
-    assert wb(1, 8, 1, 16384, 128) > 4 * 8 * 16384 and wb(1, 8, 9, 16384, 128) == 0 and wb(1, 8, 1, 16384, 96) == 0
+    assert wb(1, 8, 1, 16384, 128) > 4 * 8 * 16384 and wb(1, 8, 33, 16384, 128) == 0 and 0 < wb(1, 8, 32, 16384, 128) < wb(1, 8, 8, 16384, 128) + (16 << 20) and wb(1, 8, 1, 16384, 96) == 0
     need = wb(1, 8, 4, 1000, 128)
-    assert sk(p, p, p, p, p, p, 1, 8, 9, 1000, 128, 0, p, 1, ws, 1 << 30, None) == -4       # more than 8 queries
+    assert sk(p, p, p, p, p, p, 1, 8, 33, 1000, 128, 0, p, 1, ws, 1 << 30, None) == -4      # more than 32 queries
     assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, null, need, None) == -1
     assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, ws, need - 1, None) == -6       # workspace too small
     assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, odd, need, None) == -4          # workspace not 256-byte aligned

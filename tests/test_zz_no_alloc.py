@@ -55,6 +55,7 @@ def test_static_workspace_entry_point_equals_the_caller_workspace_one(L):
     _case(L, 8, 3, 9000, 128, 1, seed=1)          # first call: 71 key blocks per head
     _case(L, 5, 1, 700, 64, 0, seed=2)            # second call, smaller: the array still holds the first call's words
     _case(L, 8, 3, 9000, 128, 1, seed=1)
+    _case(L, 4, 20, 5000, 128, 1, seed=3)         # 9 .. 32 queries: the second pass recomputes the scores
 
 
 def test_static_workspace_entry_point_refuses_what_does_not_fit(L):
@@ -63,4 +64,4 @@ def test_static_workspace_entry_point_refuses_what_does_not_fit(L):
     assert L.ifa_splitk_workspace_bytes(B, H, Nq, Nk, d) > L.ifa_static_workspace_bytes()
     assert L.int_flash_attn_fwd_splitk_static(p, p, p, p, p, p, B, H, Nq, Nk, d, 1, p, 1, None) == -6
     assert L.ifa_status_str(-6).startswith(b"IFA_ERR_WORKSPACE")
-    assert L.int_flash_attn_fwd_splitk_static(p, p, p, p, p, p, 1, 8, 9, 1000, d, 0, p, 1, None) == -4
+    assert L.int_flash_attn_fwd_splitk_static(p, p, p, p, p, p, 1, 8, 33, 1000, d, 0, p, 1, None) == -4
