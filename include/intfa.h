@@ -91,9 +91,11 @@ int quantize_headwise_ex(const void *X, int x_dtype, long heads, long N, int d,
                          signed char *Xq, float *scale, int global_scale, void *hip_stream);
 
 /*
- * The whole input preparation of Section 3.2 for one attention call, in four launches instead of the six the
- * three separate calls take: token-level quantization of Q and K in ONE launch (which also clears the slots the
- * absmax pass of V accumulates into), then the two passes of V and the conversion of its absmax to scales.
+ * The whole input preparation of Section 3.2 for one attention call, in three launches instead of the six the
+ * three separate calls take: token-level quantization of Q and K in ONE launch, which also carries the absmax pass of V
+ * (a few workgroups per head leave the maximum of their part in the tail of V_i8: no atomics, nothing to clear); then
+ * the quantization pass of V; then one thread per head writes s_V and the tail of V_i8.  With fewer than 32 heads, or
+ * heads of fewer than 512 elements, V goes through the general two-pass path of quantize_headwise instead (four launches).
  *   Q, K, V          [heads, N, d] real activations of dtype x_dtype, heads = B*H
  *   Q_i8, K_i8, V_i8 [heads, N, d] int8 out;  s_Q, s_K [heads, N] and s_V [heads] fp32 out
  *   s_Q_mul          multiplier folded into the stored s_Q (1/sqrt(d) for the usual softmax scale; 1 for none)

@@ -121,7 +121,7 @@ def quantize_headwise(X, global_scale=False):
 
 
 def quantize_qkv(Q, K, V, s_Q_mul=1.0, out=None):
-    """The input preparation of one attention call in four launches: Q, K token-level, V tensor-level.
+    """The input preparation of one attention call in three launches: Q, K token-level, V tensor-level.
     Q, K, V [B, H, N, d] -> (Q_i8, K_i8, V_i8, s_Q [B, H, N] (times s_Q_mul), s_K [B, H, N], s_V [B, H]);
     out: optional tuple of those six tensors to write into."""
     import torch

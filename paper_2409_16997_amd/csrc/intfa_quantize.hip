@@ -120,22 +120,63 @@ template <int LPR> __device__ __forceinline__ void hadamard_row(float (&x)[8], i
 }
 
 // ---- token-level: one row = LPR lanes ---------------------------------------------------------
-// One launch serves up to two tensors of the same shape (blockIdx.y picks one: Q and K of a step), and can clear an
-// array of words on the side (the absmax slots the tensor-level quantizer of V accumulates into afterwards).
+// One launch serves up to two tensors of the same shape (Q and K of a step), can clear an array of words on the side
+// (the absmax slots the tensor-level quantizer of V accumulates into afterwards) and can carry the first pass of that
+// tensor-level quantizer along (HeadJob): blockIdx.y picks the job.
 struct TokenJob {
     const void *X;
     int8_t *Xq;
     float *scale;
     float scale_mul;
 };
+// First pass of the tensor-level quantizer without atomics and without slots to clear: HEAD_PARTS workgroups per head
+// each take a contiguous part of the head and leave the absmax of their part (fp32 bits) in the LAST 4 * HEAD_PARTS
+// bytes of that head's OUTPUT codes, which nobody writes before head_tail_finalize_kernel does (it reads them first).
+constexpr int HEAD_PARTS = 8;
+struct HeadJob {
+    const void *X;       // [heads, per_head]; null: no such job in this launch
+    int8_t *Xq;
+    long per_head;
+    int heads;
+};
+template <typename T>
+__device__ __forceinline__ void head_partial_absmax(const HeadJob &hj) {
+    if (blockIdx.x >= static_cast<unsigned>(hj.heads) * HEAD_PARTS) return;
+    const long head = blockIdx.x / HEAD_PARTS;
+    const int part = blockIdx.x % HEAD_PARTS;
+    const long chunks = hj.per_head / 8, per_part = (chunks + HEAD_PARTS - 1) / HEAD_PARTS;
+    const long c0 = part * per_part, c1 = (c0 + per_part < chunks) ? c0 + per_part : chunks;
+    float a = 0.0f;
+#pragma unroll 8
+    for (long c = c0 + threadIdx.x; c < c1; c += 256) {
+        float x[8];
+        Load8<T>::get(hj.X, head * hj.per_head + 8 * c, x);
+        a = fmaxf(a, absmax8(x));
+    }
+    a = group_max<64>(a);
+    __shared__ float wmax[4];
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        reinterpret_cast<unsigned *>(hj.Xq + (head + 1) * hj.per_head - 4 * HEAD_PARTS)[part] =
+            __float_as_uint(fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3])));
+}
+
 template <typename T, int LPR, bool HADAMARD>
 __global__ __launch_bounds__(256) void quantize_tokenwise_kernel(TokenJob j0, TokenJob j1, long rows,
-                                                                 unsigned *__restrict__ clear, long clear_words) {
+                                                                 unsigned *__restrict__ clear, long clear_words, HeadJob hj) {
     constexpr int D = LPR * 8;
     constexpr int ROWS_PER_BLOCK = 256 / LPR;
-    const TokenJob job = blockIdx.y == 0 ? j0 : j1;
+    // the head job, if any, comes last in dispatch order: V is then the most recently read tensor when the second pass
+    // of its quantizer starts, and that pass finds most of it in the Infinity Cache
+    const int y = static_cast<int>(blockIdx.y);
+    if (hj.X && y == static_cast<int>(gridDim.y) - 1) {
+        head_partial_absmax<T>(hj);
+        return;
+    }
+    const TokenJob job = y == 0 ? j0 : j1;
     const int sub = threadIdx.x % LPR;
-    if (blockIdx.y == 0)
+    if (y == 0)
         for (long i = static_cast<long>(blockIdx.x) * 256 + threadIdx.x; i < clear_words; i += static_cast<long>(gridDim.x) * 256)
             clear[i] = 0u;
     const long row_stride = static_cast<long>(gridDim.x) * ROWS_PER_BLOCK;
@@ -195,6 +236,52 @@ __global__ __launch_bounds__(256) void head_quantize_kernel(const void *__restri
     }
 }
 
+// Second pass after head_partial_absmax: everything but the last 4 * HEAD_PARTS elements of the head (where the partial
+// maxima still sit).
+template <typename T>
+__global__ __launch_bounds__(256) void head_quantize_from_parts_kernel(const void *__restrict__ X, long per_head, int8_t *__restrict__ Xq) {
+    const long head = blockIdx.y;
+    const long base = head * per_head;
+    const unsigned *parts = reinterpret_cast<const unsigned *>(Xq + base + per_head - 4 * HEAD_PARTS);
+    unsigned bits = 0u;
+#pragma unroll
+    for (int p = 0; p < HEAD_PARTS; ++p) bits = max(bits, parts[p]);   // |x| >= 0: the bit patterns order like the values
+    const float a = __uint_as_float(bits);
+    const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
+    for (long i = (static_cast<long>(blockIdx.x) * 256 + threadIdx.x) * 8; i < per_head - 4 * HEAD_PARTS;
+         i += static_cast<long>(gridDim.x) * 256 * 8) {
+        float x[8];
+        Load8<T>::get(X, base + i, x);
+        *reinterpret_cast<uint2 *>(Xq + base + i) = quant8(x, inv);
+    }
+}
+
+// Last pass: one thread per head reads the partial maxima, then writes the scale and the head's last 4 * HEAD_PARTS codes
+// over them.
+template <typename T>
+__global__ __launch_bounds__(64) void head_tail_finalize_kernel(const void *__restrict__ X, long per_head, int8_t *__restrict__ Xq,
+                                                                float *__restrict__ scale, long heads) {
+    const long head = static_cast<long>(blockIdx.x) * 64 + threadIdx.x;
+    if (head >= heads) return;
+    const long tail = head * per_head + per_head - 4 * HEAD_PARTS;
+    const unsigned *parts = reinterpret_cast<const unsigned *>(Xq + tail);
+    unsigned bits = 0u;
+#pragma unroll
+    for (int p = 0; p < HEAD_PARTS; ++p) bits = max(bits, parts[p]);
+    const float a = __uint_as_float(bits);
+    const float inv = (a == 0.0f) ? 0.0f : 127.0f / a;
+    uint2 q[4 * HEAD_PARTS / 8];
+#pragma unroll
+    for (int k = 0; k < 4 * HEAD_PARTS / 8; ++k) {
+        float x[8];
+        Load8<T>::get(X, tail + 8 * k, x);
+        q[k] = quant8(x, inv);
+    }
+#pragma unroll
+    for (int k = 0; k < 4 * HEAD_PARTS / 8; ++k) *reinterpret_cast<uint2 *>(Xq + tail + 8 * k) = q[k];
+    scale[head] = (a == 0.0f) ? 1.0f : a / 127.0f;
+}
+
 // ---- block-level: one scale per (head, block of `block` keys), single pass -----------------------
 // A workgroup owns one block: at most 128 keys x 128 channels = 16384 elements = 8 chunks of 8 per thread,
 // held in registers between the absmax and the rounding, so the activations are read once.
@@ -246,19 +333,20 @@ __global__ void head_scale_finalize_kernel(float *scale, long heads, int global_
 
 template <typename T, bool HADAMARD>
 int launch_tokenwise(const TokenJob &j0, const TokenJob &j1, int jobs, long rows, int d, unsigned *clear, long clear_words,
-                     hipStream_t st) {
+                     const HeadJob &hj, hipStream_t st) {
     const int lpr = d / 8;
     const long rows_per_block = 256 / lpr;
     long blocks = (rows + rows_per_block - 1) / rows_per_block;
     const long cap = 256L * 64 / jobs;                   // grid-stride beyond 64 blocks per CU (4 to 64 measured alike)
     if (blocks > cap) blocks = cap;
-    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(jobs)), block(256);
+    if (hj.X && blocks < static_cast<long>(hj.heads) * HEAD_PARTS) blocks = static_cast<long>(hj.heads) * HEAD_PARTS;
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(jobs + (hj.X ? 1 : 0))), block(256);
     switch (lpr) {
-    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
-    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
-    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
-    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
-    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words); break;
+    case 4: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 4, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words, hj); break;
+    case 8: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 8, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words, hj); break;
+    case 16: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 16, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words, hj); break;
+    case 32: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 32, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words, hj); break;
+    case 64: hipLaunchKernelGGL((quantize_tokenwise_kernel<T, 64, HADAMARD>), grid, block, 0, st, j0, j1, rows, clear, clear_words, hj); break;
     default: return IFA_ERR_UNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
@@ -298,11 +386,11 @@ int tokenwise_args(const void *X, int x_dtype, long rows, int d, const signed ch
 
 template <bool HADAMARD>
 int tokenwise_launch(const TokenJob &j0, const TokenJob &j1, int jobs, int x_dtype, long rows, int d, unsigned *clear,
-                     long clear_words, hipStream_t st) {
+                     long clear_words, const HeadJob &hj, hipStream_t st) {
     switch (x_dtype) {
-    case IFA_F32: return launch_tokenwise<float, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
-    case IFA_F16: return launch_tokenwise<__half, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
-    default: return launch_tokenwise<__hip_bfloat16, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, st);
+    case IFA_F32: return launch_tokenwise<float, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, hj, st);
+    case IFA_F16: return launch_tokenwise<__half, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, hj, st);
+    default: return launch_tokenwise<__hip_bfloat16, HADAMARD>(j0, j1, jobs, rows, d, clear, clear_words, hj, st);
     }
 }
 
@@ -312,7 +400,7 @@ int tokenwise_entry(const void *X, int x_dtype, long rows, int d, signed char *X
     const int rc = tokenwise_args(X, x_dtype, rows, d, Xq, scale, scale_mul);
     if (rc != IFA_OK) return rc;
     const TokenJob job = {X, reinterpret_cast<int8_t *>(Xq), scale, scale_mul};
-    return tokenwise_launch<HADAMARD>(job, job, 1, x_dtype, rows, d, nullptr, 0, static_cast<hipStream_t>(hip_stream));
+    return tokenwise_launch<HADAMARD>(job, job, 1, x_dtype, rows, d, nullptr, 0, HeadJob{nullptr, nullptr, 0, 0}, static_cast<hipStream_t>(hip_stream));
 }
 
 int headwise_args(const void *X, int x_dtype, long heads, long N, int d, const signed char *Xq, const float *scale) {
@@ -391,8 +479,37 @@ extern "C" int quantize_qkv(const void *Q, const void *K, const void *V, int x_d
     if (rc != IFA_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const TokenJob jq = {Q, reinterpret_cast<int8_t *>(Q_i8), s_Q, s_Q_mul}, jk = {K, reinterpret_cast<int8_t *>(K_i8), s_K, 1.0f};
+    const long per_head = N * d;
+    // With enough heads to fill the chip at HEAD_PARTS workgroups each, the absmax pass of V rides in the launch of Q and K
+    // (no atomics, no slots to clear) and three launches do the whole preparation; otherwise the general tensor-level
+    // path follows the launch of Q and K, which then also clears its slots.
+    if (heads >= 32 && per_head >= 64 * HEAD_PARTS) {
+        const HeadJob hj = {V, reinterpret_cast<int8_t *>(V_i8), per_head, static_cast<int>(heads)};
+        rc = tokenwise_launch<false>(jq, jk, 2, x_dtype, heads * N, d, nullptr, 0, hj, st);
+        if (rc != IFA_OK) return rc;
+        long bx = (per_head / 8 + 255) / 256;
+        const long cap = (256L * 4 + heads - 1) / heads;     // about 4 workgroups per CU in total, as in launch_headwise
+        if (bx > cap) bx = cap;
+        const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(heads)), tail_grid(static_cast<unsigned>((heads + 63) / 64));
+        int8_t *vq = reinterpret_cast<int8_t *>(V_i8);
+        switch (x_dtype) {
+        case IFA_F32:
+            hipLaunchKernelGGL((head_quantize_from_parts_kernel<float>), grid, dim3(256), 0, st, V, per_head, vq);
+            hipLaunchKernelGGL((head_tail_finalize_kernel<float>), tail_grid, dim3(64), 0, st, V, per_head, vq, s_V, heads);
+            break;
+        case IFA_F16:
+            hipLaunchKernelGGL((head_quantize_from_parts_kernel<__half>), grid, dim3(256), 0, st, V, per_head, vq);
+            hipLaunchKernelGGL((head_tail_finalize_kernel<__half>), tail_grid, dim3(64), 0, st, V, per_head, vq, s_V, heads);
+            break;
+        default:
+            hipLaunchKernelGGL((head_quantize_from_parts_kernel<__hip_bfloat16>), grid, dim3(256), 0, st, V, per_head, vq);
+            hipLaunchKernelGGL((head_tail_finalize_kernel<__hip_bfloat16>), tail_grid, dim3(64), 0, st, V, per_head, vq, s_V, heads);
+            break;
+        }
+        return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
+    }
     // one launch for Q and K, which also clears the slots the absmax pass of V accumulates into
-    rc = tokenwise_launch<false>(jq, jk, 2, x_dtype, heads * N, d, reinterpret_cast<unsigned *>(s_V), heads, st);
+    rc = tokenwise_launch<false>(jq, jk, 2, x_dtype, heads * N, d, reinterpret_cast<unsigned *>(s_V), heads, HeadJob{nullptr, nullptr, 0, 0}, st);
     if (rc != IFA_OK) return rc;
     return headwise_launch(V, x_dtype, heads, N, d, V_i8, s_V, 0, st, true);
 }
