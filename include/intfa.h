@@ -175,6 +175,8 @@ int int_flash_attn_fwd_splitk(const signed char *Q_i8, const signed char *K_i8, 
  * (ifa_static_workspace_bytes() bytes, 16 MiB, held by every GPU the library runs on until the process ends).  The
  * call allocates nothing and frees nothing.  A shape with ifa_splitk_workspace_bytes(...) beyond that size is refused
  * with IFA_ERR_WORKSPACE before any launch (16 MiB hold, e.g., B*H = 128 heads of 16384 keys at Nq = 1).
+ * ifa_static_workspace_bytes() doubles as the set-up call: it looks the array's device address up for the current
+ * device (once per device; otherwise the first int_flash_attn_fwd_splitk_static on that device does it).
  * Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams, two threads) race
  * on it and must be serialized by the caller.  Nothing in it needs clearing between calls: every word a call reads
  * it has written before.

@@ -586,7 +586,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int D, bool CAUSAL, typename OutT>
+template <int D, bool CAUSAL, bool VB, typename OutT>
 __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
     const int8_t *__restrict__ Q, const int8_t *__restrict__ K, const int8_t *__restrict__ V,
     const float *__restrict__ sQ, const float *__restrict__ sK, const float *__restrict__ sV,
@@ -655,10 +655,17 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) { o[v] = 0.0f; acc0[v] = ACC_START_I; }
 
+    // s_V: one scalar per head, or (VB) one per key block of this head, read through the scalar cache
+    const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
+    float sv_prev = 1.0f;
     wait_vmcnt<2 * PER_BLOCK>();                                 // my pieces of block 0 have landed (blocks 1 and 2 may be in flight)
     __syncthreads();                                             // everyone's have
     for (int jb = 0; jb < nblocks; ++jb) {                       // line 7
         const int st = jb % NSTAGE, j0 = jb * BC;
+        // with one V scale per key block the running output is kept in units of the current block's scale (see the kernel above)
+        const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
+        const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
+        sv_prev = sv_j;
         const lds_ptr ks = kbuf + st * BC * D, vs = vbuf + st * BC * D, sk = skbuf + st * BC * 4;
 
         // line 9 for key tile `wave`
@@ -726,14 +733,15 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_narrow_kernel(
             pacc = __builtin_amdgcn_mfma_i32_32x32x32_i8(vop, pf, mt == 0 ? acc0 : pacc, 0, 0, 0);
         }
         l = __builtin_fmaf(l, alpha, static_cast<float>(psum));
+        const float alpha_o = VB ? alpha * oscale : alpha;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[v] = __builtin_fmaf(o[v], alpha, -(ACC_START_F - __int_as_float(pacc[v])));
+        for (int v = 0; v < 16; ++v) o[v] = __builtin_fmaf(o[v], alpha_o, -(ACC_START_F - __int_as_float(pacc[v])));
     }
     wait_all_memory();                                           // requests past the last block: nothing of mine stays in flight
 
     // lines 15-17 for d tile `wave` (d = 32 * wave + 8 * (v / 4) + 4 * g + v % 4 of query r)
     const float lt = l + swap32(l);
-    const float f = sV[head] * ACC_UNIT / lt;
+    const float f = (VB ? sv_prev : sVh[0]) * ACC_UNIT / lt;
     if (q_head < Nq && wave < KS) {
         OutT *orow = O + (static_cast<long>(head) * Nq + q_head) * D + 32 * wave + 4 * g;
 #pragma unroll
@@ -1278,11 +1286,11 @@ int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *s
 #define IFA_NARROW_MAX_Q 64
 #endif
 
-template <int D, bool CAUSAL, typename OutT>
+template <int D, bool CAUSAL, bool VB, typename OutT>
 int launch_narrow(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK, const float *sV,
                   int heads, int Nq, int Nk, void *O, hipStream_t st) {
     const long wgs = static_cast<long>(heads) * ((Nq + NARROW_BR - 1) / NARROW_BR);
-    hipLaunchKernelGGL((int_flash_attn_fwd_narrow_kernel<D, CAUSAL, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0, st,
+    hipLaunchKernelGGL((int_flash_attn_fwd_narrow_kernel<D, CAUSAL, VB, OutT>), dim3(static_cast<unsigned>(wgs)), dim3(THREADS), 0, st,
                        Q, K, V, sQ, sK, sV, heads, Nq, Nk, static_cast<OutT *>(O));
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
@@ -1290,11 +1298,11 @@ int launch_narrow(const int8_t *Q, const int8_t *K, const int8_t *V, const float
 template <int D, bool CAUSAL, bool VB>
 int launch_fwd_dtype(const int8_t *Q, const int8_t *K, const int8_t *V, const float *sQ, const float *sK,
                      const float *sV, int heads, int Nq, int Nk, void *O, int o_dtype, hipStream_t st) {
-    if (!VB && Nq <= IFA_NARROW_MAX_Q) {
+    if (Nq <= IFA_NARROW_MAX_Q) {
         switch (o_dtype) {
-        case IFA_F32: return launch_narrow<D, CAUSAL, float>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
-        case IFA_F16: return launch_narrow<D, CAUSAL, __half>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
-        default: return launch_narrow<D, CAUSAL, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        case IFA_F32: return launch_narrow<D, CAUSAL, VB, float>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        case IFA_F16: return launch_narrow<D, CAUSAL, VB, __half>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
+        default: return launch_narrow<D, CAUSAL, VB, __hip_bfloat16>(Q, K, V, sQ, sK, sV, heads, Nq, Nk, O, st);
         }
     }
     switch (o_dtype) {
@@ -1513,7 +1521,12 @@ void *static_workspace() {
 }
 }  // namespace
 
-extern "C" long ifa_static_workspace_bytes(void) { return STATIC_WORKSPACE_BYTES; }
+// Also the set-up call: it resolves the array's address on the current device, so that a later
+// int_flash_attn_fwd_splitk_static on this device (under graph capture, say) has no set-up left to do.
+extern "C" long ifa_static_workspace_bytes(void) {
+    (void)static_workspace();
+    return STATIC_WORKSPACE_BYTES;
+}
 
 extern "C" int int_flash_attn_fwd_splitk_static(const signed char *Q_i8, const signed char *K_i8, const signed char *V_i8,
                                                 const float *s_Q, const float *s_K, const float *s_V, int B, int H, int Nq,

@@ -469,6 +469,23 @@ def test_few_query_calls_equal_the_square_kernel_rows(ifa, Nq, d, out_dtype):
         assert torch.equal(few, full[:, :, N - Nq:]), (Nq, d, causal)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Nq", [1, 7, 33, 64])
+def test_few_query_calls_with_blockwise_v_scales_equal_the_square_kernel_rows(ifa, Nq, d):
+    # the same with one V scale per key block (the running output is carried in units of the current block's scale)
+    H, N = 3, 1231
+    rng = np.random.default_rng(Nq * 17 + d)
+    Qq, Kq, Vq, sQ, sK, _ = random_int8_problem(rng, H, N, d, score_sigma=2.0)
+    sVb = rng.uniform(0.005, 0.05, (H, -(-N // ifa.block_cols(d, True)))).astype(np.float32)
+    args = lambda q, sq: (dev(q[None]), dev(Kq[None]), dev(Vq[None]), dev(sq[None]), dev(sK[None]), dev(sVb[None]))
+    for causal in (False, True):
+        full = ifa.int_flash_attn_fwd(*args(Qq, sQ), causal=causal, out_dtype=torch.float32)
+        few = ifa.int_flash_attn_fwd(*args(np.ascontiguousarray(Qq[:, N - Nq:]), np.ascontiguousarray(sQ[:, N - Nq:])),
+                                     causal=causal, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(few, full[:, :, N - Nq:]), (Nq, d, causal)
+
+
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("Nq,Nk,d", [(1, 16384, 128), (1, 1, 128), (7, 300, 64), (32, 4097, 128), (64, 127, 64), (50, 2048, 128)])
 def test_few_query_calls_against_the_oracle(ifa, Nq, Nk, d, causal):
