@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libintfa.so")
-SOURCES = ["intfa_attention.hip", "intfa_attention_half.hip", "intfa_quantize.hip"]
+SOURCES = ["intfa_attention.hip", "intfa_attention_fewq.hip", "intfa_attention_half.hip", "intfa_quantize.hip"]
 
 # Packed-fp32 instructions are switched off on purpose (the flag is a device-side feature; the host
 # pass warns that it does not know it, which is harmless).  No fast-math: the quantizer is bit-exact.
