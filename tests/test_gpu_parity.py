@@ -511,7 +511,8 @@ def test_few_query_calls_against_the_oracle(ifa, Nq, Nk, d, causal):
 
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("Nq,Nk,H", [(1, 16384, 8), (1, 1, 3), (1, 129, 1), (3, 1000, 5), (8, 4097, 8), (5, 300, 16), (2, 20000, 2), (8, 8, 4),
-                                      (9, 4097, 8), (32, 16384, 2), (20, 1000, 5), (32, 32, 3), (17, 300, 16), (12, 500, 100)])
+                                      (9, 4097, 8), (32, 16384, 2), (20, 1000, 5), (32, 32, 3), (17, 300, 16), (12, 500, 100),
+                                      (8, 258, 16), (32, 1026, 4)])   # the last run of key blocks is masked entirely for the early queries
 def test_key_split_calls_equal_the_sequential_walk(ifa, Nq, Nk, H, d):
     # The key-split path forms P on the grid of the running maximum of the sequential walk (it knows every block's
     # maximum before it forms any P), so it differs from the one-workgroup-per-head kernel only by the order of the
