@@ -106,7 +106,7 @@ template <int D> struct RowState {
 template <int D, bool DIAG, bool VB, bool DBG>
 __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk, lds_ptr ks_next, const LaneOffsets<D> &lo,
                                               const v4i (&qf)[D / 32], float nq2, int wave, int lane, int klimit, int last_tile, int clear_tiles,
-                                              int g, float oscale, const Prefetch &nx, bool preload_next,
+                                              int g, float oscale, const float *sv_next_ptr, float &sv_next, const Prefetch &nx, bool preload_next,
                                               v4i (&kfirst)[D / 32], RowState<D> &st, const DebugDump &dbg, long dbg_row, int dbg_j0, int dbg_jb, int dbg_nq) {
     constexpr int KS = D / 32, DT = D / 32;
     const int last = DIAG ? last_tile : 3;           // last active 32-key tile (wave-uniform)
@@ -279,8 +279,12 @@ __device__ __forceinline__ void process_block(lds_ptr ks, lds_ptr vs, lds_ptr sk
     st.l = __builtin_fmaf(st.l, alpha, static_cast<float>(psum));   // line 12 (this lane's half of the keys)
 
     if (!DIAG) {
+        // (VB) the next block's V scale: a scalar load placed where every counter is waited to zero anyway.  Anywhere
+        // else, waiting for it means lgkmcnt(0), i.e. waiting for every LDS operand read in flight as well.
+        if (VB) sv_next = *sv_next_ptr;
         wait_all_memory();                                       // my part of the next block has landed in LDS
         __syncthreads();                                         // everyone's has, and the current buffers are free again
+        if (VB) asm volatile("" : "+s"(sv_next));
         if (preload_next) load_k(kfirst, ks_next, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -377,19 +381,23 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
     // crosses, the ragged last block -- run the masked code.
     const int nfull = min(nblocks, CAUSAL ? min(Nk / BC, (first_q + shift + 1) / BC) : Nk / BC);
 
+    // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_c].  The scale of the coming block
+    // is requested (a scalar load) in front of a wait for everything and handed on by the unmasked blocks: a scalar
+    // load still in flight anywhere else turns every LDS wait behind it into a wait for all LDS reads.
+    const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
+    float sv_prev = 1.0f;
+    float sv_cur = VB ? sVh[0] : 1.0f;
     wait_all_memory();
     __syncthreads();
+    if (VB) asm volatile("" : "+s"(sv_cur));
     v4i kfirst[D / 32];                                          // K operands of the first key tile of the coming block
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk) kfirst[kk] = *reinterpret_cast<LDS_AS const v4i *>(k_operand<D>(kbuf, lo, kk));
 
-    // s_V: one scalar per head, or (VB) one per key block of this head: sV [heads, T_c]
-    const float *sVh = VB ? sV + static_cast<long>(head) * T_c : sV + head;
-    float sv_prev = 1.0f;
     for (int jb = 0; jb < nfull; ++jb) {                         // line 7
         const int cur = jb & 1, nxt = cur ^ 1;
-        const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
-        const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
+        const float sv_j = sv_cur;
+        const float oscale = VB ? uniform(sv_prev * __builtin_amdgcn_rcpf(sv_j)) : 1.0f;
         sv_prev = sv_j;
         const int j1 = (jb + 1) * BC;                            // line 8 for the next block, asynchronous
         const bool more = jb + 1 < nblocks;
@@ -397,7 +405,8 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
                              vbuf + nxt * BC * D, skbuf + nxt * BC * 4};
         // the staged copies are awaited and the workgroup barrier is met inside, between the second GEMM and the fold
         process_block<D, false, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf + nxt * BC * D, lo, qf, nq2,
-                                         wave, lane, 0, 3, 4, g, oscale, pf, jb + 1 < nfull, kfirst, st, dbg, dbg_row, jb * BC, jb, Nq);
+                                         wave, lane, 0, 3, 4, g, oscale, sVh + (VB ? min(jb + 1, T_c - 1) : 0), sv_cur, pf, jb + 1 < nfull, kfirst, st, dbg,
+                                         dbg_row, jb * BC, jb, Nq);
     }
     // At most two masked blocks follow (the diagonal band of 128 queries crosses at most two key blocks, and the
     // ragged last block is one of them or, without a mask, the only one).  They are written out one after the
@@ -412,11 +421,11 @@ __global__ __launch_bounds__(THREADS, 2) void int_flash_attn_fwd_kernel(
         const int wmin = CAUSAL ? min(first_q + 32 * wave + shift - j0, tail) : tail;   // klimit of the wavefront's first row
         if (wlim >= 0) {                                         // wave-uniform: this wavefront sees part of the block
             const Prefetch none = {rK, rV, rSK, NOWHERE, NOWHERE, kbuf, vbuf, skbuf};   // masked blocks request nothing
-            const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
-            const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
+            const float sv_j = VB ? (jb == nfull ? sv_cur : uniform(sVh[jb])) : 1.0f;
+            const float oscale = VB ? uniform(sv_prev * __builtin_amdgcn_rcpf(sv_j)) : 1.0f;
             sv_prev = sv_j;
             process_block<D, true, VB, DBG>(kbuf + cur * BC * D, vbuf + cur * BC * D, skbuf + cur * BC * 4, kbuf, lo, qf, nq2, wave, lane,
-                                            klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, none, false, kfirst, st, dbg,
+                                            klimit, min(3, wlim >> 5), max(0, (wmin + 1) >> 5), g, oscale, sVh, sv_cur, none, false, kfirst, st, dbg,
                                             dbg_row, j0, jb, Nq);
         }
     };

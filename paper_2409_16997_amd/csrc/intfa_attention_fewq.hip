@@ -129,7 +129,7 @@ __global__ __launch_bounds__(THREADS) void int_flash_attn_fwd_narrow_kernel(
         const int st = jb % NSTAGE, j0 = jb * BC;
         // with one V scale per key block the running output is kept in units of the current block's scale (see the kernel above)
         const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
-        const float oscale = VB ? uniform(sv_prev / sv_j) : 1.0f;
+        const float oscale = VB ? uniform(sv_prev * __builtin_amdgcn_rcpf(sv_j)) : 1.0f;
         sv_prev = sv_j;
         const lds_ptr ks = kbuf + st * BC * D, vs = vbuf + st * BC * D, sk = skbuf + st * BC * 4;
 
