@@ -472,7 +472,8 @@ int launch_fwd(const int8_t *Q, const int8_t *K, const int8_t *V, const float *s
     return hipGetLastError() == hipSuccess ? IFA_OK : IFA_ERR_HIP;
 }
 
-// Calls with at most this many queries per head go to the narrow kernel (measured against the kernel above).
+// Calls with at most this many queries per head go to the narrow kernel of intfa_attention_fewq.hip (measured against
+// the fused kernel).
 #ifndef IFA_NARROW_MAX_Q
 #define IFA_NARROW_MAX_Q 64
 #endif

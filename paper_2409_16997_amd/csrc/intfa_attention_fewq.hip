@@ -23,7 +23,7 @@ namespace {
 using namespace ifa_tiles;
 
 // ---- few queries, many keys (a decode step, a short chunk of a prefill) ---------------------------------------
-// With at most a few dozen queries per head the kernel above would keep three of its four wavefronts idle and one
+// With at most a few dozen queries per head the fused kernel would keep three of its four wavefronts idle and one
 // workgroup per head cannot fill the chip; what limits such a call is how fast K and V stream in.  Here the four
 // wavefronts of a workgroup share ONE group of 32 queries and split each 128-key block instead:
 //     wavefront w computes S^T for key tile w (32 keys; 4 MFMAs), scales it, takes its minimum / maximum;
@@ -31,7 +31,7 @@ using namespace ifa_tiles;
 //     wavefront w computes the 16 P bytes per lane of its key tile and leaves them in LDS (second barrier);
 //     wavefront w then computes the d tile w (32 of the d columns) of O^T = V^T P^T over ALL 128 keys (4 MFMAs,
 //     P operands of the four key tiles from LDS) and folds it into its 16 registers of the running output.
-// Every number is computed by the same instruction sequence on the same operands as in the kernel above (the
+// Every number is computed by the same instruction sequence on the same operands as in the fused kernel (the
 // integer sums are exact, the extremum is order-independent, the row sum l is taken over the same P dwords), so
 // the output is bit-identical to the corresponding rows of a square call: still Algorithm 1 at B_c = 128.
 // K and V come in through a ring of NSTAGE blocks (one workgroup per CU: there are few workgroups anyway), filled
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(THREADS) void int_flash_attn_fwd_narrow_kernel(
     __syncthreads();                                             // everyone's have
     for (int jb = 0; jb < nblocks; ++jb) {                       // line 7
         const int st = jb % NSTAGE, j0 = jb * BC;
-        // with one V scale per key block the running output is kept in units of the current block's scale (see the kernel above)
+        // with one V scale per key block the running output is kept in units of the current block's scale (as in the fused kernel)
         const float sv_j = VB ? uniform(sVh[jb]) : 1.0f;
         const float oscale = VB ? uniform(sv_prev * __builtin_amdgcn_rcpf(sv_j)) : 1.0f;
         sv_prev = sv_j;
@@ -222,12 +222,12 @@ __global__ __launch_bounds__(THREADS) void int_flash_attn_fwd_narrow_kernel(
 }
 
 // ---- few queries, many keys, any number of heads: the key axis split across workgroups, exactly ----------------
-// One workgroup per head (the kernel above) cannot fill the chip when there are few heads, and even with 128 of them
+// One workgroup per head (the narrow kernel) cannot fill the chip when there are few heads, and even with 128 of them
 // it is bound by its own block-to-block latency.  Splitting the keys of a head over workgroups is not Algorithm 1 as
 // long as each part rounds P on the grid of ITS OWN running maximum; it is Algorithm 1 once the maximum after every
 // key block is known before any P is formed.  With at most SPLIT_MAX_Q queries per head the scores are small next to
 // K and V (4 N_q bytes per key against 2 d), so they go through memory:
-//   pass 1 (splitk_scores_kernel)  streams K, computes line 9 exactly as the kernels above do (same MFMA chain, same
+//   pass 1 (splitk_scores_kernel)  streams K, computes line 9 exactly as the other kernels do (same MFMA chain, same
 //           scaling) and writes the scaled scores a, the minimum of every (32-key tile, query) -- the maxima of line 10
 //           -- and the minimum of every (run of blocks, query);
 //   pass 2 (splitk_pv_kernel)      streams V and the scores; the running maximum in front of a workgroup's first block
