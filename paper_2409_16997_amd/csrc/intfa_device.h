@@ -40,14 +40,12 @@ constexpr float ACC_UNIT = 67108864.0f;               // 2^26: accumulator steps
 // Without the mask every workgroup of a head walks all of its K and V, and what a group streams at a time should fit
 // the XCD's 4 MB L2: 4 MB / (K + V bytes of a head), between 1 and 4 (long sequences run 2-3 % faster with 1 or 2
 // heads than with 4).  Under the mask the query blocks of a head are uneven and run heaviest first, and more heads
-// per group even the 64 workgroup slots of an XCD out better: 8 heads when a head has at least 10 query blocks
-// (N = 2048, d = 128: +5 % over 4; N = 4096: +3-4 %, although 8 heads' K and V are twice the L2 there -- workgroups
-// that run together are at the same depth of their heads and touch the same keys; N = 8192, 16384: no difference;
-// no gain with fewer query blocks; 12 or 16 heads per group are no better than 8).
+// per group even the 64 workgroup slots of an XCD out better: 8 heads when their K and V still fit the L2 and a head
+// has at least 10 query blocks (N = 2048, d = 128: +5 % over 4; no gain below, a loss once 8 heads exceed the L2).
 constexpr int HEAD_GROUP = 4;
 inline int head_group_for(bool causal, long kv_bytes_per_head, int T_r) {
     const long fit = (4L << 20) / (kv_bytes_per_head > 0 ? kv_bytes_per_head : 1);
-    if (causal) return T_r >= 10 ? 8 : HEAD_GROUP;
+    if (causal) return (fit >= 8 && T_r >= 10) ? 8 : HEAD_GROUP;
     return static_cast<int>(fit < 1 ? 1 : (fit > HEAD_GROUP ? HEAD_GROUP : fit));
 }
 
