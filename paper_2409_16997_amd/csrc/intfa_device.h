@@ -41,7 +41,9 @@ constexpr float ACC_UNIT = 67108864.0f;               // 2^26: accumulator steps
 // the XCD's 4 MB L2: 4 MB / (K + V bytes of a head), between 1 and 4 (long sequences run 2-3 % faster with 1 or 2
 // heads than with 4).  Under the mask the query blocks of a head are uneven and run heaviest first, and more heads
 // per group even the 64 workgroup slots of an XCD out better: 8 heads when their K and V still fit the L2 and a head
-// has at least 10 query blocks (N = 2048, d = 128: +5 % over 4; no gain below, a loss once 8 heads exceed the L2).
+// has at least 10 query blocks (N = 2048, d = 128: +5 % over 4; no gain below).  Once 8 heads exceed the L2 (N = 4096)
+// 8 per group still measures 2-4 % faster, but the XCDs then fetch K and V from memory twice over (FETCH_SIZE 1.99 x
+// the algorithmic reads against 1.19 x): not taken.
 constexpr int HEAD_GROUP = 4;
 inline int head_group_for(bool causal, long kv_bytes_per_head, int T_r) {
     const long fit = (4L << 20) / (kv_bytes_per_head > 0 ? kv_bytes_per_head : 1);
