@@ -102,6 +102,8 @@ def test_argument_validation_happens_on_the_host(L):
     assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 1, odd, need, None) == -4          # workspace not 256-byte aligned
     assert sk(p, p, p, p, p, p, 1, 8, 4, 2, 128, 1, p, 1, ws, need, None) == -4              # causal with Nk < Nq
     assert sk(p, p, p, p, p, p, 1, 8, 4, 1000, 128, 0, p, 5, ws, need, None) == -3
+    assert L.ifa_static_workspace_bytes() == 16 << 20                                         # also without a GPU: the set-up part is skipped
+    assert L.int_flash_attn_fwd_splitk_static(p, p, p, p, p, p, 4, 32, 8, 16384, 128, 1, p, 1, None) == -6   # 86 MB needed
     hf = L.int_flash_attn_fwd_half
     assert hf(p, p, null, p, p, 1, 1, 128, 128, 0, p, 1, None) == -1 and hf(p, p, p, p, p, 1, 0, 128, 128, 0, p, 1, None) == -2
     assert hf(p, p, p, p, p, 1, 1, 128, 128, 0, p, -1, None) == -3 and hf(p, p, p, p, p, 1, 1, 128, 256, 0, p, 1, None) == -4
