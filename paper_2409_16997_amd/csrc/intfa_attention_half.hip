@@ -186,7 +186,7 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
             for (int v = 0; v < 16; ++v) a[mt][v] = -INFINITY;
         }
     }
-    load_v(0, 0);                                                 // first V^T operands go out before the last tile is scaled
+    if constexpr (MASKED) load_v(0, 0);                           // first V^T operands go out before the last tile is scaled
 #pragma unroll
     for (int mt = 0; mt < NT; ++mt)
         if (mt == last) scale_tile(mt, sacc[mt & 1], skr[mt & 1]);
@@ -200,17 +200,59 @@ __device__ __forceinline__ void process_block_half(lds_ptr ks, lds_ptr vs, lds_p
     h2 ph[NT][8];
     float psum = 0.0f;
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    auto p_pair = [&](int mt, int c) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][2 * c], sq2, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][2 * c + 1], sq2, -m_new));
+        const h2 w = {(_Float16)p0, (_Float16)p1};
+        ph[mt][c] = w;
+        psum = __builtin_amdgcn_fdot2(w, ones, psum, false);
+    };
+    if constexpr (!MASKED) {
+        // Unmasked blocks: the second GEMM runs key tile by key tile over all d tiles, with the weights of the NEXT key
+        // tile computed between its MFMAs at raised wave priority (two exps per MFMA hide behind it); each V^T operand
+        // is re-requested for the next key tile right after the MFMA that read it has issued.
+        h8 vt[DT][2];
+        auto load_v1 = [&](int mt, int dt, int s_) {
+            const int koff = (32 * mt + 16 * s_) * (2 * D);
+            const h4 t0 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(lds_xor(vs, 64 * dt, lo.v0) + koff)));
+            const h4 t1 = __builtin_bit_cast(h4, __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<LDS_AS s4 *>(lds_xor(vs, 64 * dt, lo.v0) + 8 * (2 * D) + koff)));
+            vt[dt][s_] = h8{t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
+        };
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) { load_v1(0, dt, 0); load_v1(0, dt, 1); }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) p_pair(0, c);
+        __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                if (mt == 0) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) st.o[dt][v] *= alpha;
+                }
+#pragma unroll
+                for (int s_ = 0; s_ < 2; ++s_) {
+                    const h8 pb = {ph[mt][4 * s_][0], ph[mt][4 * s_][1], ph[mt][4 * s_ + 1][0], ph[mt][4 * s_ + 1][1],
+                                   ph[mt][4 * s_ + 2][0], ph[mt][4 * s_ + 2][1], ph[mt][4 * s_ + 3][0], ph[mt][4 * s_ + 3][1]};
+                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vt[dt][s_], pb, st.o[dt], 0, 0, 0);
+                    if (mt + 1 < NT) load_v1(mt + 1, dt, s_);
+                }
+                if (mt + 1 < NT) {
+#pragma unroll
+                    for (int q = 0; q < 8 / DT; ++q) p_pair(mt + 1, dt * (8 / DT) + q);
+                }
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        st.l = __builtin_fmaf(st.l, alpha, psum);
+        return;
+    }
 #pragma unroll
     for (int mt = 0; mt < NT; ++mt) {
         if (mt <= last) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][2 * c], sq2, -m_new));
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(a[mt][2 * c + 1], sq2, -m_new));
-                const h2 w = {(_Float16)p0, (_Float16)p1};
-                ph[mt][c] = w;
-                psum = __builtin_amdgcn_fdot2(w, ones, psum, false);
-            }
+            for (int c = 0; c < 8; ++c) p_pair(mt, c);
         }
     }
     st.l = __builtin_fmaf(st.l, alpha, psum);
