@@ -10,7 +10,8 @@
  *     [N, d]; batch and heads are independent copies of it.
  *   - Calls enqueue kernels on a HIP stream and return without synchronising.  The stream is
  *     the explicit argument where there is one, else the one given to ifa_set_stream()
- *     (the null stream until then).
+ *     (the null stream until then).  No call synchronises, allocates or enqueues a memset, so the
+ *     explicit-stream calls may be recorded into a HIP graph and replayed.
  *   - Return value: IFA_OK (0) or a negative ifa_status.  On any error nothing is enqueued.
  *     Arguments are validated on the host before a launch, so an unsupported shape is an
  *     error code, never a device fault.
