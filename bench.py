@@ -197,9 +197,8 @@ def main():
                 Qq, Kq, Vq, sQ, sK, sV = ifa.quantize_qkv(Q, K, V, s_Q_mul=fold, out=state.get("bufs"))
                 state.update(Qq=Qq, Kq=Kq, Vq=Vq, sQ=sQ, sK=sK, sV=sV, bufs=(Qq, Kq, Vq, sQ, sK, sV))
             else:
-                Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=fold)
-                Kq, sK = ifa.quantize_tokenwise(K)
-                state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK)
+                Qq, Kq, sQ, sK = ifa.quantize_qk(Q, K, s_Q_mul=fold, out=state.get("qk"))    # Q and K token-level, one launch
+                state.update(Qq=Qq, Kq=Kq, sQ=sQ, sK=sK, qk=(Qq, Kq, sQ, sK))
                 if vblock:
                     Vq, sV = ifa.quantize_blockwise(V, ifa.block_cols(w.d, w.causal))
                     state.update(Vq=Vq, sV=sV)

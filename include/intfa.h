@@ -92,6 +92,18 @@ int quantize_headwise_ex(const void *X, int x_dtype, long heads, long N, int d,
                          signed char *Xq, float *scale, int global_scale, void *hip_stream);
 
 /*
+ * Token-level quantization of Q and K (Section 3.2) in ONE launch: what the per-block-V and half-INT8 paths need in
+ * front of the attention call (their V goes through quantize_blockwise, or stays fp16).
+ *   Q, K        [rows, d] real activations of dtype x_dtype (same shape; rows = B*H*N)
+ *   Q_i8, K_i8  [rows, d] int8 out;  s_Q, s_K [rows] fp32 out;  s_Q_mul folded into the stored s_Q (> 0)
+ *   hadamard    non-zero: both tensors are rotated by H_d first, as in quantize_tokenwise_hadamard (Section 5)
+ * Results are bit-identical to two quantize_tokenwise_ex (or quantize_tokenwise_hadamard) calls, whose argument rules
+ * apply; nothing is enqueued on an error.
+ */
+int quantize_qk(const void *Q, const void *K, int x_dtype, long rows, int d, signed char *Q_i8, signed char *K_i8,
+                float *s_Q, float *s_K, float s_Q_mul, int hadamard, void *hip_stream);
+
+/*
  * The whole input preparation of Section 3.2 for one attention call, in three launches instead of the six the
  * three separate calls take: token-level quantization of Q and K in ONE launch, which also carries the absmax pass of V
  * (a few workgroups per head leave the maximum of their part in the tail of V_i8: no atomics, nothing to clear); then

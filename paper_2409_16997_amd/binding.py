@@ -19,6 +19,7 @@ SIGNATURES = {
     "quantize_tokenwise_hadamard": (_i, [_vp, _i, _l, _i, _vp, _vp, ctypes.c_float, _vp]),
     "quantize_headwise": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i]),
     "quantize_headwise_ex": (_i, [_vp, _i, _l, _l, _i, _vp, _vp, _i, _vp]),
+    "quantize_qk": (_i, [_vp, _vp, _i, _l, _i, _vp, _vp, _vp, _vp, ctypes.c_float, _i, _vp]),
     "quantize_qkv": (_i, [_vp, _vp, _vp, _i, _l, _l, _i, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp]),
     "int_flash_attn_fwd": (_i, [_vp] * 6 + [_i] * 5 + [_vp]),
     "int_flash_attn_fwd_ex": (_i, [_vp] * 6 + [_i] * 5 + [_vp, _i, _vp]),
@@ -138,6 +139,24 @@ def quantize_qkv(Q, K, V, s_Q_mul=1.0, out=None):
                               _dev(v8, torch.int8), _dev(sq, torch.float32), _dev(sk, torch.float32), _dev(sv, torch.float32),
                               float(s_Q_mul), _stream()), "quantize_qkv")
     return q8, k8, v8, sq, sk, sv
+
+
+def quantize_qk(Q, K, s_Q_mul=1.0, hadamard=False, out=None):
+    """Q and K token-level in one launch.  Q, K [..., d] of one shape -> (Q_i8, K_i8, s_Q [...] (times s_Q_mul), s_K [...]);
+    out: optional tuple of those four tensors to write into."""
+    import torch
+    assert Q.shape == K.shape and Q.dtype == K.dtype
+    d = Q.shape[-1]
+    rows = Q.numel() // d
+    if out is None:
+        q8, k8 = (torch.empty(Q.shape, dtype=torch.int8, device=Q.device) for _ in range(2))
+        sq, sk = (torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device) for _ in range(2))
+    else:
+        q8, k8, sq, sk = out
+    _check(lib().quantize_qk(_dev(Q), _dev(K), _dtype_enum(Q), rows, d, _dev(q8, torch.int8), _dev(k8, torch.int8),
+                             _dev(sq, torch.float32), _dev(sk, torch.float32), float(s_Q_mul), int(bool(hadamard)), _stream()),
+           "quantize_qk")
+    return q8, k8, sq, sk
 
 
 def quantize_blockwise(X, block_keys):

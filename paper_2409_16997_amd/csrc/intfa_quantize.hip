@@ -470,6 +470,18 @@ extern "C" int quantize_headwise(const void *X, int x_dtype, long heads, long N,
     return quantize_headwise_ex(X, x_dtype, heads, N, d, Xq, scale, global_scale, ifa_current_stream());
 }
 
+extern "C" int quantize_qk(const void *Q, const void *K, int x_dtype, long rows, int d, signed char *Q_i8, signed char *K_i8,
+                           float *s_Q, float *s_K, float s_Q_mul, int hadamard, void *hip_stream) {
+    int rc = tokenwise_args(Q, x_dtype, rows, d, Q_i8, s_Q, s_Q_mul);
+    if (rc == IFA_OK) rc = tokenwise_args(K, x_dtype, rows, d, K_i8, s_K, 1.0f);
+    if (rc != IFA_OK) return rc;
+    const TokenJob jq = {Q, reinterpret_cast<int8_t *>(Q_i8), s_Q, s_Q_mul}, jk = {K, reinterpret_cast<int8_t *>(K_i8), s_K, 1.0f};
+    const HeadJob none = {nullptr, nullptr, 0, 0};
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return hadamard ? tokenwise_launch<true>(jq, jk, 2, x_dtype, rows, d, nullptr, 0, none, st)
+                    : tokenwise_launch<false>(jq, jk, 2, x_dtype, rows, d, nullptr, 0, none, st);
+}
+
 extern "C" int quantize_qkv(const void *Q, const void *K, const void *V, int x_dtype, long heads, long N, int d,
                             signed char *Q_i8, signed char *K_i8, signed char *V_i8, float *s_Q, float *s_K, float *s_V,
                             float s_Q_mul, void *hip_stream) {

@@ -27,7 +27,7 @@ def declared_symbols():
 def test_header_declares_the_north_star_calls():
     names = declared_symbols()
     for must in ("quantize_tokenwise", "quantize_headwise", "int_flash_attn_fwd", "int_flash_attn_fwd_ex",
-                 "quantize_tokenwise_ex", "quantize_headwise_ex", "quantize_qkv", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "int_flash_attn_fwd_splitk", "ifa_splitk_workspace_bytes", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
+                 "quantize_tokenwise_ex", "quantize_headwise_ex", "quantize_qk", "quantize_qkv", "quantize_tokenwise_hadamard", "quantize_blockwise", "int_flash_attn_fwd_vblock", "int_flash_attn_fwd_vblock_rect", "int_flash_attn_fwd_half", "int_flash_attn_fwd_half_rect", "ifa_block_cols_half", "int_flash_attn_fwd_rect", "int_flash_attn_fwd_splitk", "ifa_splitk_workspace_bytes", "ifa_block_cols", "ifa_debug_fwd", "ifa_set_stream", "ifa_status_str"):
         assert must in names
 
 
@@ -77,6 +77,10 @@ def test_argument_validation_happens_on_the_host(L):
     qx = L.quantize_tokenwise_ex
     assert qx(p, 1, 10, 128, p, p, 0.0, None) == -2 and qx(p, 1, 10, 128, p, p, float("nan"), None) == -2
     assert qx(p, 1, 10, 128, null, p, 1.0, None) == -1
+    qk = L.quantize_qk
+    assert qk(p, null, 1, 10, 128, p, p, p, p, 1.0, 0, None) == -1 and qk(p, p, 1, 10, 128, p, p, p, null, 1.0, 1, None) == -1
+    assert qk(p, p, 1, 0, 128, p, p, p, p, 1.0, 0, None) == -2 and qk(p, p, 1, 10, 128, p, p, p, p, -1.0, 0, None) == -2
+    assert qk(p, p, 4, 10, 128, p, p, p, p, 1.0, 0, None) == -3 and qk(p, odd, 1, 10, 128, p, p, p, p, 1.0, 0, None) == -4
     h = L.quantize_headwise
     assert h(p, 1, 4, 128, 64, p, null, 0) == -1
     assert h(p, 1, 0, 128, 64, p, p, 0) == -2

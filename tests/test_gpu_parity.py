@@ -167,6 +167,25 @@ def test_quantize_qkv_equals_the_three_separate_calls(ifa, dtype, B, H, N, d):
     assert float(rsv[0, 0]) == 1.0 and not bool(rv[0, 0].any())
 
 
+@pytest.mark.parametrize("hadamard", [False, True])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape", [(2, 3, 77, 64), (4, 8, 500, 128), (1, 1, 1, 32)])
+def test_quantize_qk_equals_the_two_separate_calls(ifa, shape, dtype, hadamard):
+    # Q and K in one launch against the single-tensor entry points (themselves bit-exact against the oracle above),
+    # bit for bit, with and without the Hadamard rotation; the second call writes into the first call's buffers
+    g = torch.Generator(device="cuda").manual_seed(sum(shape))
+    Q, K = (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(dtype) for _ in range(2))
+    K[0, 0, 0] = 0                                         # an all-zero row: scale 1, codes 0
+    fold = 1.0 / math.sqrt(shape[-1])
+    rq, rsq = ifa.quantize_tokenwise(Q, scale_mul=fold, hadamard=hadamard)
+    rk, rsk = ifa.quantize_tokenwise(K, hadamard=hadamard)
+    out = ifa.quantize_qk(Q * 0.25, K * 2.0, s_Q_mul=1.0, hadamard=hadamard)
+    got = ifa.quantize_qk(Q, K, s_Q_mul=fold, hadamard=hadamard, out=out)
+    torch.cuda.synchronize()
+    for a, b in zip(got, (rq, rk, rsq, rsk)):
+        assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ int32 accumulators: bit-exact
 
 def _oracle_block_pv(P, V, Bc):
