@@ -1,4 +1,5 @@
-"""Seeded random shapes through every attention entry point, every row compared with the oracle at the strict bar:
+"""Seeded random shapes through every attention entry point, every row compared with the oracle at the strict bar
+(and, in the second test, through every quantizer entry point, bit for bit):
 the fused kernel (square and N_q != N_k), the few-query kernel, per-block V scales, the key-split path and the
 half-INT8 variant; d in {64, 128}, 1-8 heads, ragged N_q, N_k up to 1500, with and without the causal mask, flat
 to peaked score distributions.  The committed parity cases fix their shapes by hand; this one draws them."""
@@ -70,3 +71,66 @@ def test_random_shapes_meet_the_strict_bar_on_every_row(ifa, seed):
         assert np.isfinite(got).all(), (seed, case, desc)
         res = oracle.compare_up_to_ties(got, Qq, Kq, Vq, sQ, sK, sV, causal, Bc)
         assert np.all(res["err"] <= 1e-3 * res["scale"]), (seed, case, desc, float((res["err"] / res["scale"]).max()))
+
+
+def _widen(t):
+    return t.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_quantizer_calls_equal_the_oracle_bit_for_bit(ifa, seed):
+    # every quantizer entry point on drawn shapes, dtypes and value distributions (outlier channels, values near the
+    # bottom of the fp32 range of the scale, all-zero rows): codes and scales against the oracle's, bit for bit
+    rng = np.random.default_rng(seed)
+    dtypes = [torch.float32, torch.float16, torch.bfloat16]
+    for case in range(70):
+        kind = str(rng.choice(["token", "hadamard", "head", "global", "block", "qkv", "qk"]))
+        d = int(rng.choice([32, 64, 128, 256, 512])) if kind in ("token", "hadamard", "qk") else int(rng.choice([64, 128]))
+        H = int(rng.choice([1, 2, 3, 7, 32, 40]))
+        N = int(rng.choice([1, 5, 64, 129, 1000, 2051]))
+        if kind in ("head", "global", "qkv") and (N * d) % 8:
+            N += 1
+        dt = dtypes[int(rng.integers(0, 3))]
+        dist = str(rng.choice(["normal", "outlier", "tiny", "zero_rows"]))
+        g = torch.Generator(device="cpu").manual_seed(1000 * seed + case)
+
+        def draw():
+            x = torch.randn((H, N, d), generator=g)
+            if dist == "outlier":
+                x[..., :: max(1, d // 4)] *= 50
+            if dist == "tiny":
+                x *= 1e-6
+            if dist == "zero_rows":
+                x[:, ::3] = 0
+            return x.to(dt).cuda()
+
+        X = draw()
+        desc = (seed, case, kind, d, H, N, str(dt), dist)
+        half = np.float32(0.5)
+        if kind == "token":
+            got = ifa.quantize_tokenwise(X, scale_mul=0.5)
+            rq, rs = oracle.quantize_tokenwise(_widen(X))
+            ref = (rq, (rs * half).astype(np.float32))
+        elif kind == "hadamard":
+            got = ifa.quantize_tokenwise(X, scale_mul=d ** -0.5, hadamard=True)
+            ref = oracle.quantize_tokenwise_hadamard(_widen(X), scale_mul=d ** -0.5)
+        elif kind in ("head", "global"):
+            got = ifa.quantize_headwise(X, global_scale=(kind == "global"))
+            ref = oracle.quantize_headwise(_widen(X), global_scale=(kind == "global"))
+        elif kind == "block":
+            got = ifa.quantize_blockwise(X, 128)
+            ref = oracle.quantize_blockwise(_widen(X), 128)
+        elif kind == "qkv":
+            K, V = draw(), draw()
+            got = ifa.quantize_qkv(X, K, V, s_Q_mul=0.5)
+            got = ifa.quantize_qkv(X, K, V, s_Q_mul=0.5, out=got)           # again, into what the first call left
+            (rq, rsq), (rk, rsk), (rv, rsv) = (oracle.quantize_tokenwise(_widen(X)), oracle.quantize_tokenwise(_widen(K)),
+                                               oracle.quantize_headwise(_widen(V)))
+            ref = (rq, rk, rv, (rsq * half).astype(np.float32), rsk, rsv)
+        else:
+            K = draw()
+            got = ifa.quantize_qk(X, K, s_Q_mul=0.5)
+            (rq, rsq), (rk, rsk) = oracle.quantize_tokenwise(_widen(X)), oracle.quantize_tokenwise(_widen(K))
+            ref = (rq, rk, (rsq * half).astype(np.float32), rsk)
+        for a, b in zip(got, ref):
+            assert np.array_equal(a.cpu().numpy(), b), desc
