@@ -115,6 +115,46 @@ def decode_bench(args, torch, ifa):
     print(json.dumps(result))
 
 
+def shape_bench(args, torch, ifa):
+    """Profiling aid, not the headline benchmark: the attention call alone on a chosen shape (Nq != Nk allowed), on N(0,1)
+    fp16 activations quantized beforehand.  Prints one JSON line per shape (several shapes separated by ';' share the
+    process and its clock state) with the time per launch and the time a workgroup holds its slot per key block."""
+    dev = torch.device("cuda:0")
+    for spec in args.shape.split(";"):
+        B, H, Nq, Nk, d, causal = (int(x) for x in spec.split(","))
+        g = torch.Generator(device=dev).manual_seed(20240916)
+        Q = torch.randn((B, H, Nq, d), device=dev, generator=g, dtype=torch.float16)
+        K, V = (torch.randn((B, H, Nk, d), device=dev, generator=g, dtype=torch.float16) for _ in range(2))
+        Qq, sQ = ifa.quantize_tokenwise(Q, scale_mul=1.0 / math.sqrt(d))
+        Kq, sK = ifa.quantize_tokenwise(K)
+        Vq, sV = ifa.quantize_headwise(V)
+        O = torch.empty((B, H, Nq, d), dtype=torch.float16, device=dev)
+        fn = lambda: ifa.int_flash_attn_fwd(Qq, Kq, Vq, sQ, sK, sV, causal=bool(causal), out=O)
+        t_pre = time.perf_counter()
+        while time.perf_counter() - t_pre < 2 * PREWARM_S:
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        Bc = ifa.block_cols(d, bool(causal))
+        T_r = -(-Nq // 128)
+        blocks = sum(min(Nk - 1, (qb + 1) * 128 - 1 + Nk - Nq) // Bc + 1 for qb in range(T_r)) if causal else T_r * -(-Nk // Bc)
+        ops = 4.0 * B * H * d * (sum(Nk - Nq + i + 1 for i in range(Nq)) if causal else Nq * Nk)
+        print(json.dumps({"metric": "int8_attention_fwd_tops (attention call alone, profiling aid)", "value": round(ops / (ms * 1e-3) / 1e12, 1),
+                          "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                          "config": {"workload": f"B={B} H={H} Nq={Nq} Nk={Nk} d={d} causal={causal}", "workgroups": B * H * T_r,
+                                     "key_blocks_per_workgroup": round(blocks / T_r, 2)},
+                          "slot_us_per_workgroup": round(ms * 1e3 * 512 / (B * H * T_r), 2),
+                          "frac_of_int8_mfma_peak": round(ops / (ms * 1e-3) / (PEAK_INT8_TOPS * 1e12), 4)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -132,6 +172,9 @@ def main():
                     help="not the headline benchmark: time one decode-shaped attention call (Nq <= 32 queries per head against Nk "
                          "keys, causal) through the one-workgroup-per-head kernel and through the key-split path, K and V already "
                          "quantized and resident in HBM; prints one JSON line with an HBM roofline for the key-split call")
+    ap.add_argument("--shape", default=None, metavar="B,H,Nq,Nk,d,causal[;...]",
+                    help="profiling aid, not the headline benchmark: time the attention call alone on these shapes (quantized "
+                         "beforehand), one JSON line each, with the time a workgroup holds one of the chip's 512 slots")
     ap.add_argument("--zero-operands", action="store_true",
                     help="profiling aid, not a benchmark: all-zero activations, i.e. the same instruction stream on operands "
                          "that toggle no bits -- the difference to the real run is what the clock the chip settles at under "
@@ -153,6 +196,8 @@ def main():
         sys.exit("bench.py needs a GPU")
     if args.decode:
         return decode_bench(args, torch, ifa)
+    if args.shape:
+        return shape_bench(args, torch, ifa)
     dev = torch.device("cuda:0")
     w = workloads.WORKLOADS[args.workload]
     sh = (w.B, w.H, w.N, w.d)

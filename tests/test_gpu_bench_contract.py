@@ -49,3 +49,15 @@ def test_bench_decode_mode_prints_an_hbm_roofline_line():
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and 0 < rf["frac"] < 1 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     assert d["cpu_baseline"]["kind"] == "oracle" and d["parity_max_rel_err_vs_oracle"] <= 1e-3 + 2.0 ** -10
     assert d["max_rel_diff_between_the_two_paths"] <= 2.0 ** -9
+
+
+def test_bench_shape_mode_prints_one_line_per_shape():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--shape", "1,8,384,640,128,1;2,4,256,256,64,0", "--steps", "3", "--warmup", "1"],
+                       capture_output=True, text=True, timeout=250)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [json.loads(ln) for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 2
+    assert lines[0]["config"]["workgroups"] == 8 * 3 and lines[0]["config"]["key_blocks_per_workgroup"] == 4.0   # 3, 4 and 5 blocks
+    assert lines[1]["config"]["key_blocks_per_workgroup"] == 2.0
+    for d in lines:
+        assert d["unit"] == "TOPS" and d["value"] > 0 and d["ms_per_step"] > 0 and 0 < d["frac_of_int8_mfma_peak"] < 1
